@@ -1,0 +1,176 @@
+/*
+ * ud.h -- C ABI of the GPU-centric feature-row gather for AMD MI355X (gfx950).
+ *
+ * The operation is the one PyTorch-Direct (arXiv 2101.07956) builds its case
+ * on: a 2-D feature array whose row index is the node ID (Section 2.2) stays in
+ * host memory that the GPU can dereference directly (Section 3, Figure 2b;
+ * Section 4.1), and a minibatch tensor features[neighbor_id] (Listings 1-2) is
+ * produced by GPU threads reading the selected rows over the host link and
+ * writing them, in ID-list order (Section 4.5), to a dense tensor in GPU
+ * memory.  No CPU gather, no staging buffer, no DMA call.
+ *
+ * Conventions for every call
+ *   - returns a ud_status; UD_OK is 0.  Output arguments are written only on UD_OK
+ *     unless stated otherwise.
+ *   - "device pointer" = an address the GPU can dereference (HBM, or pinned host
+ *     memory mapped into the GPU's address space); "host pointer" = an address
+ *     the CPU can dereference.
+ *   - tables and outputs are contiguous row-major, row stride = D elements.
+ *   - the library is bound to the HIP device that is current in the calling
+ *     thread; it never changes the current device.
+ *   - not thread-safe per table handle; distinct handles and distinct streams
+ *     may be used from distinct threads.
+ */
+#ifndef UD_H
+#define UD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    UD_OK = 0,
+    UD_ERR_INVALID_ARG = 1,        /* null pointer, non-positive size, unknown enum, misaligned pointer */
+    UD_ERR_UNSUPPORTED = 2,        /* valid request the library has no code path for */
+    UD_ERR_OOM = 3,                /* host pinning or device allocation failed */
+    UD_ERR_INDEX_OUT_OF_RANGE = 4, /* an ID outside [0, N) was met by a gather */
+    UD_ERR_HIP = 5                 /* any other HIP runtime failure; see ud_last_hip_error */
+} ud_status;
+
+/* element type of the table, and of the output */
+typedef enum {
+    UD_F32 = 0,        /* 4-byte elements in, 4-byte elements out (bit copy) */
+    UD_F16 = 1,        /* 2-byte elements in, 2-byte elements out (bit copy) */
+    UD_F16_TO_F32 = 2  /* IEEE binary16 in, binary32 out: exact widening, subnormals kept,
+                          NaN keeps sign and payload and is returned quiet */
+} ud_dtype;
+
+/* element type of the ID list */
+typedef enum { UD_I64 = 0, UD_I32 = 1 } ud_itype;
+
+/* flags for ud_alloc_table */
+enum {
+    UD_TABLE_COHERENT = 0,     /* fine-grained (host-coherent) pinned memory: the default */
+    UD_TABLE_NONCOHERENT = 1   /* coarse-grained pinned memory: GPU caches may keep lines, so CPU
+                                  writes made while a kernel runs may not be seen by it */
+};
+
+typedef struct ud_table ud_table; /* opaque handle, owned by the library */
+
+/*
+ * Feature table in pinned, GPU-mapped host memory (the paper's "unified
+ * tensor" storage, Section 4.1: physically in host memory, directly
+ * accessible by the GPU, ordinary memory to the CPU).
+ * N rows of D elements; elem is UD_F32 (4-byte) or UD_F16 (2-byte).  The memory
+ * is uninitialised; the caller fills it through ud_table_host_ptr.  It belongs
+ * to the library until ud_free_table.
+ * Errors: UD_ERR_INVALID_ARG (N < 1, D < 1, bad elem/flags, t == NULL, size
+ * overflow), UD_ERR_OOM (the host could not pin that much).
+ */
+ud_status ud_alloc_table(int64_t N, int64_t D, ud_dtype elem, unsigned flags, ud_table **t);
+
+/*
+ * Device-resident variant: a new table in HBM holding rows [row0, row0 + n) of
+ * src (Section 2.2 notes that a table small enough may simply live in GPU
+ * memory).  The copy is complete when the call returns.  The result has no
+ * host pointer.  src must be a host table.
+ * Errors: UD_ERR_INVALID_ARG (bad range, src NULL or already device-resident),
+ * UD_ERR_OOM (HBM exhausted).
+ */
+ud_status ud_table_to_device(const ud_table *src, int64_t row0, int64_t n, ud_table **t);
+
+/* Host address of row 0 (NULL is stored for a device-resident table). */
+ud_status ud_table_host_ptr(const ud_table *t, void **p);
+/* Device pointer of row 0: what ud_gather takes as `table`. */
+ud_status ud_table_device_ptr(const ud_table *t, const void **p);
+/* Shape and element type as given at allocation. */
+ud_status ud_table_shape(const ud_table *t, int64_t *N, int64_t *D, ud_dtype *elem);
+/* Releases the handle and its memory.  NULL is a no-op.  No gather that reads
+ * the table may still be in flight. */
+ud_status ud_free_table(ud_table *t);
+
+/*
+ * out[i, j] = conv(table[idx[i], j])   for 0 <= i < M, 0 <= j < D
+ * (features[neighbor_id] of Listings 1-2, result in GPU memory, row order =
+ * ID-list order as Section 4.5 requires).
+ *
+ *   table  device pointer to N x D elements (host-mapped or HBM), aligned to its
+ *          element size; read only.
+ *   dtype  UD_F32, UD_F16 or UD_F16_TO_F32 (conv = identity on bits, or widening).
+ *   idx    device pointer (HBM) to M IDs of type itype; the paper's index is a
+ *          GPU tensor (Table 1).  Duplicates allowed.  Never read by the CPU.
+ *   out    device pointer (HBM) to M x D output elements (4-byte for UD_F32 and
+ *          UD_F16_TO_F32, 2-byte for UD_F16), aligned to its element size; must
+ *          not overlap table.
+ *   stream a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Asynchronous: arguments are validated on the host, kernels are enqueued on
+ * stream, and the call returns.  M == 0 is UD_OK and enqueues nothing.
+ * An ID < 0 or >= N is never dereferenced: its output row is left unwritten and
+ * the smallest such position is recorded for ud_gather_status; other rows of
+ * the same call are still gathered.  Negative IDs are not wrapped.
+ * Errors (synchronous): UD_ERR_INVALID_ARG (N < 1, D < 1, M < 0, unknown enum,
+ * NULL or misaligned pointer with M > 0, sizes whose byte counts overflow
+ * int64), UD_ERR_HIP (launch failure).
+ * The library allocates nothing per call; the first call on a device allocates
+ * one 8-byte error word in HBM that lives until the process ends.
+ */
+ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                    const void *idx, ud_itype itype, int64_t M,
+                    void *out, void *stream);
+
+/*
+ * Kernel tuning for ud_gather_tuned; a zero field means "choose automatically".
+ *   lanes_per_row    power of two in [1, 64]: lanes of a wavefront that share one row
+ *   chunks_per_lane  1..4: 16-byte chunks of one row each lane keeps in flight
+ *   rows_in_flight   1, 2, 4 or 8: rows each lane group loads before storing any
+ *   max_blocks       cap on workgroups (grid-stride beyond it)
+ *   flags            UD_TUNE_* bits
+ */
+typedef struct {
+    int32_t lanes_per_row;
+    int32_t chunks_per_lane;
+    int32_t rows_in_flight;
+    int32_t max_blocks;
+    uint32_t flags;
+} ud_tuning;
+
+enum {
+    UD_TUNE_NT_LOAD = 1u,       /* non-temporal (streaming) loads from the table */
+    UD_TUNE_NT_STORE = 2u,      /* non-temporal stores to out */
+    UD_TUNE_ELEMENTWISE = 4u    /* one lane per element, rows straddling wavefronts: the layout of
+                                   the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
+                                   the comparison point and as the fallback for odd alignments */
+};
+
+/* ud_gather with explicit kernel parameters (for the tuning loop and for tests that
+ * exercise every kernel instantiation).  tuning == NULL behaves like ud_gather.
+ * Extra error: UD_ERR_INVALID_ARG for a field outside the ranges above,
+ * UD_ERR_UNSUPPORTED for a combination with no instantiation. */
+ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                          const void *idx, ud_itype itype, int64_t M,
+                          void *out, void *stream, const ud_tuning *tuning);
+
+/* The parameters ud_gather would pick for this shape and table alignment (no launch). */
+ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning *plan);
+
+/*
+ * Waits for stream, then reports ID errors of gathers on the current device
+ * since the previous ud_gather_status call: UD_OK and *bad_pos = -1 if none,
+ * else UD_ERR_INDEX_OUT_OF_RANGE and *bad_pos = the smallest offending position
+ * i (position in idx, not the ID).  bad_pos is written in both cases and may
+ * be NULL.  The record is cleared.  It is shared by all streams of a device.
+ */
+ud_status ud_gather_status(void *stream, int64_t *bad_pos);
+
+/* Static, human-readable name of a status code. */
+const char *ud_status_str(ud_status s);
+/* HIP's message for the most recent UD_ERR_HIP / UD_ERR_OOM in this thread ("" if none). */
+const char *ud_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UD_H */

@@ -1,0 +1,369 @@
+// C-ABI boundary of the row-gather library: table allocation in pinned,
+// GPU-mapped host memory (the storage of the paper's "unified tensor",
+// PyTorch-Direct Section 4.1), the device-resident variant, argument checks,
+// kernel selection and the asynchronous ID-error record.  Host code only; the
+// kernels live in ud_gather_*.hip.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "ud.h"
+#include "ud_internal.h"
+
+struct ud_table {
+    void *host;      // CPU address of row 0, nullptr when device-resident
+    void *dev;       // GPU address of row 0
+    int64_t N, D;
+    ud_dtype elem;
+    bool device_resident;
+};
+
+namespace {
+
+thread_local char g_hip_msg[256] = "";
+
+ud_status hip_fail(hipError_t e, const char *what)
+{
+    std::snprintf(g_hip_msg, sizeof g_hip_msg, "%s: %s", what, hipGetErrorString(e));
+    (void)hipGetLastError(); // do not leave the error for an unrelated later call
+    return e == hipErrorOutOfMemory ? UD_ERR_OOM : UD_ERR_HIP;
+}
+
+int elem_bytes(ud_dtype t) { return t == UD_F32 ? 4 : 2; }
+int out_elem_bytes(ud_dtype t) { return t == UD_F16 ? 2 : 4; }
+
+bool mul3_overflows(int64_t a, int64_t b, int64_t c, int64_t *r)
+{
+    int64_t ab;
+    return __builtin_mul_overflow(a, b, &ab) || __builtin_mul_overflow(ab, c, r);
+}
+
+// One error word per device, allocated on the first gather and kept for the
+// life of the process.
+constexpr int kMaxDevices = 64;
+std::mutex g_err_mutex;
+unsigned long long *g_err_word[kMaxDevices] = {};
+
+ud_status error_word(unsigned long long **w)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices)
+        return UD_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_err_mutex);
+    if (!g_err_word[dev]) {
+        unsigned long long *p = nullptr;
+        e = hipMalloc(reinterpret_cast<void **>(&p), sizeof *p);
+        if (e != hipSuccess)
+            return hip_fail(e, "hipMalloc(error word)");
+        const unsigned long long init = ud::kNoBadIndex;
+        e = hipMemcpy(p, &init, sizeof init, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(p);
+            return hip_fail(e, "hipMemcpy(error word)");
+        }
+        g_err_word[dev] = p;
+    }
+    *w = g_err_word[dev];
+    return UD_OK;
+}
+
+int next_pow2(int64_t x)
+{
+    int p = 1;
+    while (p < x && p < 64)
+        p <<= 1;
+    return p;
+}
+
+// Largest number of 16-byte chunks any row can overlap, given the base address
+// and the row pitch: the row start offsets modulo 16 cycle with period <= 16.
+int64_t max_chunks_per_row(uintptr_t base, int64_t row_bytes)
+{
+    int64_t worst_head = 0;
+    for (int k = 0; k < 16; ++k) {
+        const int64_t head = static_cast<int64_t>((base + static_cast<uintptr_t>(k) * static_cast<uintptr_t>(row_bytes)) & 15u);
+        if (head > worst_head)
+            worst_head = head;
+    }
+    return (worst_head + row_bytes + 15) >> 4;
+}
+
+constexpr int kDefaultMaxBlocks = 1 << 22;
+
+ud::Plan auto_plan(const void *table, int64_t D, ud_dtype dtype)
+{
+    const int64_t row_bytes = D * elem_bytes(dtype);
+    const int64_t nch = max_chunks_per_row(reinterpret_cast<uintptr_t>(table), row_bytes);
+    ud::Plan p{};
+    p.flags = 0;
+    p.max_blocks = kDefaultMaxBlocks;
+    if (nch <= 64) {
+        p.lanes_per_row = next_pow2(nch);
+        p.chunks_per_lane = 1;
+        p.rows_in_flight = 8;
+    } else {
+        p.lanes_per_row = 64;
+        const int64_t passes = (nch + 63) / 64;
+        p.chunks_per_lane = passes > 4 ? 4 : static_cast<int>(passes);
+        p.rows_in_flight = p.chunks_per_lane == 2 ? 4 : 2;
+    }
+    return p;
+}
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+} // namespace
+
+extern "C" {
+
+ud_status ud_alloc_table(int64_t N, int64_t D, ud_dtype elem, unsigned flags, ud_table **t)
+{
+    if (!t || N < 1 || D < 1 || (elem != UD_F32 && elem != UD_F16) || (flags & ~1u))
+        return UD_ERR_INVALID_ARG;
+    int64_t bytes;
+    if (mul3_overflows(N, D, elem_bytes(elem), &bytes))
+        return UD_ERR_INVALID_ARG;
+    const unsigned hip_flags =
+        hipHostMallocMapped | ((flags & UD_TABLE_NONCOHERENT) ? hipHostMallocNonCoherent : hipHostMallocCoherent);
+    void *host = nullptr;
+    hipError_t e = hipHostMalloc(&host, static_cast<size_t>(bytes), hip_flags);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipHostMalloc");
+    void *dev = nullptr;
+    e = hipHostGetDevicePointer(&dev, host, 0);
+    if (e != hipSuccess) {
+        (void)hipHostFree(host);
+        return hip_fail(e, "hipHostGetDevicePointer");
+    }
+    ud_table *h = new (std::nothrow) ud_table{host, dev, N, D, elem, false};
+    if (!h) {
+        (void)hipHostFree(host);
+        return UD_ERR_OOM;
+    }
+    *t = h;
+    return UD_OK;
+}
+
+ud_status ud_table_to_device(const ud_table *src, int64_t row0, int64_t n, ud_table **t)
+{
+    if (!src || !t || src->device_resident || row0 < 0 || n < 1 || row0 > src->N - n)
+        return UD_ERR_INVALID_ARG;
+    const int64_t row_bytes = src->D * elem_bytes(src->elem);
+    const size_t bytes = static_cast<size_t>(n) * static_cast<size_t>(row_bytes);
+    void *dev = nullptr;
+    hipError_t e = hipMalloc(&dev, bytes);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipMalloc(table)");
+    e = hipMemcpy(dev, static_cast<const char *>(src->host) + row0 * row_bytes, bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(dev);
+        return hip_fail(e, "hipMemcpy(table)");
+    }
+    ud_table *h = new (std::nothrow) ud_table{nullptr, dev, n, src->D, src->elem, true};
+    if (!h) {
+        (void)hipFree(dev);
+        return UD_ERR_OOM;
+    }
+    *t = h;
+    return UD_OK;
+}
+
+ud_status ud_table_host_ptr(const ud_table *t, void **p)
+{
+    if (!t || !p)
+        return UD_ERR_INVALID_ARG;
+    *p = t->host;
+    return UD_OK;
+}
+
+ud_status ud_table_device_ptr(const ud_table *t, const void **p)
+{
+    if (!t || !p)
+        return UD_ERR_INVALID_ARG;
+    *p = t->dev;
+    return UD_OK;
+}
+
+ud_status ud_table_shape(const ud_table *t, int64_t *N, int64_t *D, ud_dtype *elem)
+{
+    if (!t)
+        return UD_ERR_INVALID_ARG;
+    if (N)
+        *N = t->N;
+    if (D)
+        *D = t->D;
+    if (elem)
+        *elem = t->elem;
+    return UD_OK;
+}
+
+ud_status ud_free_table(ud_table *t)
+{
+    if (!t)
+        return UD_OK;
+    const hipError_t e = t->device_resident ? hipFree(t->dev) : hipHostFree(t->host);
+    delete t;
+    return e == hipSuccess ? UD_OK : hip_fail(e, "free");
+}
+
+ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning *plan)
+{
+    if (!plan || D < 1 || (dtype != UD_F32 && dtype != UD_F16 && dtype != UD_F16_TO_F32))
+        return UD_ERR_INVALID_ARG;
+    int64_t row_bytes;
+    if (__builtin_mul_overflow(D, static_cast<int64_t>(elem_bytes(dtype)), &row_bytes) || row_bytes > INT64_MAX - 64)
+        return UD_ERR_INVALID_ARG;
+    const ud::Plan p = auto_plan(table, D, dtype);
+    plan->lanes_per_row = p.lanes_per_row;
+    plan->chunks_per_lane = p.chunks_per_lane;
+    plan->rows_in_flight = p.rows_in_flight;
+    plan->max_blocks = p.max_blocks;
+    plan->flags = p.flags;
+    return UD_OK;
+}
+
+ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                          const void *idx, ud_itype itype, int64_t M,
+                          void *out, void *stream, const ud_tuning *tuning)
+{
+    if (N < 1 || D < 1 || M < 0)
+        return UD_ERR_INVALID_ARG;
+    if (dtype != UD_F32 && dtype != UD_F16 && dtype != UD_F16_TO_F32)
+        return UD_ERR_INVALID_ARG;
+    if (itype != UD_I64 && itype != UD_I32)
+        return UD_ERR_INVALID_ARG;
+    int64_t table_bytes, out_bytes;
+    if (mul3_overflows(N, D, elem_bytes(dtype), &table_bytes) || mul3_overflows(M, D, out_elem_bytes(dtype), &out_bytes))
+        return UD_ERR_INVALID_ARG;
+    if (table_bytes > INT64_MAX - 64)
+        return UD_ERR_INVALID_ARG;
+
+    ud::Plan plan = auto_plan(table, D, dtype);
+    if (tuning) {
+        if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE))
+            return UD_ERR_INVALID_ARG;
+        if (tuning->lanes_per_row < 0 || tuning->lanes_per_row > 64 ||
+            (tuning->lanes_per_row && !is_pow2(tuning->lanes_per_row)))
+            return UD_ERR_INVALID_ARG;
+        if (tuning->chunks_per_lane < 0 || tuning->chunks_per_lane > 4)
+            return UD_ERR_INVALID_ARG;
+        const int u = tuning->rows_in_flight;
+        if (u != 0 && u != 1 && u != 2 && u != 4 && u != 8)
+            return UD_ERR_INVALID_ARG;
+        if (tuning->max_blocks < 0)
+            return UD_ERR_INVALID_ARG;
+        plan.flags = tuning->flags;
+        if (tuning->lanes_per_row)
+            plan.lanes_per_row = tuning->lanes_per_row;
+        if (tuning->chunks_per_lane)
+            plan.chunks_per_lane = tuning->chunks_per_lane;
+        if (tuning->rows_in_flight)
+            plan.rows_in_flight = tuning->rows_in_flight;
+        else if (tuning->chunks_per_lane && plan.rows_in_flight * plan.chunks_per_lane > 8)
+            plan.rows_in_flight = plan.chunks_per_lane >= 3 ? 2 : 4;
+        if (tuning->max_blocks)
+            plan.max_blocks = tuning->max_blocks;
+        if (plan.rows_in_flight * plan.chunks_per_lane > 8)
+            return UD_ERR_UNSUPPORTED;
+    }
+
+    if (M == 0)
+        return UD_OK;
+    if (!table || !idx || !out)
+        return UD_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(table) % elem_bytes(dtype) || reinterpret_cast<uintptr_t>(out) % out_elem_bytes(dtype) ||
+        reinterpret_cast<uintptr_t>(idx) % (itype == UD_I64 ? 8 : 4))
+        return UD_ERR_INVALID_ARG;
+
+    ud::GatherArgs a{};
+    a.table = static_cast<const char *>(table);
+    a.N = N;
+    a.D = D;
+    a.idx = idx;
+    a.itype = itype;
+    a.M = M;
+    a.out = out;
+    const ud_status es = error_word(&a.err);
+    if (es != UD_OK)
+        return es;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (plan.flags & UD_TUNE_ELEMENTWISE)
+        e = ud::launch_elementwise(a, dtype, plan, s);
+    else if (dtype == UD_F32)
+        e = ud::launch_chunked_f32(a, plan, s);
+    else if (dtype == UD_F16)
+        e = ud::launch_chunked_f16(a, plan, s);
+    else
+        e = ud::launch_chunked_f16_to_f32(a, plan, s);
+    if (e == hipErrorInvalidValue)
+        return UD_ERR_UNSUPPORTED;
+    if (e != hipSuccess)
+        return hip_fail(e, "kernel launch");
+    return UD_OK;
+}
+
+ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                    const void *idx, ud_itype itype, int64_t M,
+                    void *out, void *stream)
+{
+    return ud_gather_tuned(table, N, D, dtype, idx, itype, M, out, stream, nullptr);
+}
+
+ud_status ud_gather_status(void *stream, int64_t *bad_pos)
+{
+    if (bad_pos)
+        *bad_pos = -1;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return hip_fail(e, "hipStreamSynchronize");
+    int dev = 0;
+    e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipGetDevice");
+    unsigned long long *w = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_err_mutex);
+        if (dev >= 0 && dev < kMaxDevices)
+            w = g_err_word[dev];
+    }
+    if (!w)
+        return UD_OK; // no gather has run on this device yet
+    unsigned long long v = ud::kNoBadIndex;
+    e = hipMemcpy(&v, w, sizeof v, hipMemcpyDeviceToHost);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipMemcpy(error word)");
+    if (v == ud::kNoBadIndex)
+        return UD_OK;
+    const unsigned long long init = ud::kNoBadIndex;
+    e = hipMemcpy(w, &init, sizeof init, hipMemcpyHostToDevice);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipMemcpy(error word reset)");
+    if (bad_pos)
+        *bad_pos = static_cast<int64_t>(v);
+    return UD_ERR_INDEX_OUT_OF_RANGE;
+}
+
+const char *ud_status_str(ud_status s)
+{
+    switch (s) {
+    case UD_OK: return "UD_OK";
+    case UD_ERR_INVALID_ARG: return "UD_ERR_INVALID_ARG";
+    case UD_ERR_UNSUPPORTED: return "UD_ERR_UNSUPPORTED";
+    case UD_ERR_OOM: return "UD_ERR_OOM";
+    case UD_ERR_INDEX_OUT_OF_RANGE: return "UD_ERR_INDEX_OUT_OF_RANGE";
+    case UD_ERR_HIP: return "UD_ERR_HIP";
+    }
+    return "UD_ERR_UNKNOWN";
+}
+
+const char *ud_last_hip_error(void) { return g_hip_msg; }
+
+} // extern "C"

@@ -1,0 +1,46 @@
+// Internal interface between the C-ABI boundary and the gfx950 kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ud.h"
+
+namespace ud {
+
+// Sentinel held by the device error word while no bad ID has been seen.
+constexpr unsigned long long kNoBadIndex = 0x7fffffffffffffffull;
+
+struct GatherArgs {
+    const char *table;       // device pointer to row 0
+    int64_t N, D;
+    const void *idx;         // device pointer, M entries
+    int itype;               // UD_I64 / UD_I32
+    int64_t M;
+    void *out;               // device pointer, M x D output elements
+    unsigned long long *err; // device error word (atomic min of bad positions)
+};
+
+// Resolved kernel parameters (every field concrete, see ud_tuning).
+struct Plan {
+    int lanes_per_row;   // power of two, 1..64
+    int chunks_per_lane; // 1..4
+    int rows_in_flight;  // 1, 2, 4, 8
+    int max_blocks;      // > 0
+    unsigned flags;      // UD_TUNE_*
+};
+
+// Wavefronts per workgroup used by every kernel here.
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlockThreads = 64 * kWavesPerBlock;
+
+// Enqueue the chunked (row-per-lane-group) gather.  Returns hipErrorInvalidValue
+// if (dtype, plan) has no instantiation.
+hipError_t launch_chunked_f32(const GatherArgs &a, const Plan &p, hipStream_t s);
+hipError_t launch_chunked_f16(const GatherArgs &a, const Plan &p, hipStream_t s);
+hipError_t launch_chunked_f16_to_f32(const GatherArgs &a, const Plan &p, hipStream_t s);
+
+// Enqueue the one-lane-per-element gather.
+hipError_t launch_elementwise(const GatherArgs &a, int dtype, const Plan &p, hipStream_t s);
+
+} // namespace ud

@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ud():
+    import paper_2101_07956_amd as m
+    return m
+
+
+def test_library_exports_every_symbol_the_header_declares(ud):
+    header = open(os.path.join(ROOT, "include", "ud.h")).read()
+    declared = set(re.findall(r"\b(ud_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(ud.EXPORTS)
+    lib = ctypes.CDLL(ud.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(ud):
+    names = [ud.ud_status_str(s) for s in range(6)]
+    assert names == ["UD_OK", "UD_ERR_INVALID_ARG", "UD_ERR_UNSUPPORTED", "UD_ERR_OOM",
+                     "UD_ERR_INDEX_OUT_OF_RANGE", "UD_ERR_HIP"]
+    assert ud.ud_status_str(99) == "UD_ERR_UNKNOWN"
+
+
+def _gather(ud, table=0x1000, N=10, D=4, dtype=0, idx=0x2000, itype=0, M=5, out=0x3000, tuning=None):
+    args = [table, N, D, dtype, idx, itype, M, out, None]
+    if tuning is None:
+        return ud.binding.raw_status("ud_gather", *args)
+    return ud.binding.raw_status("ud_gather_tuned", *args, ctypes.byref(tuning))
+
+
+def test_gather_rejects_bad_scalars_before_any_device_work(ud):
+    inv = ud.UD_ERR_INVALID_ARG
+    assert _gather(ud, N=0) == inv
+    assert _gather(ud, N=-3) == inv
+    assert _gather(ud, D=0) == inv
+    assert _gather(ud, M=-1) == inv
+    assert _gather(ud, dtype=3) == inv
+    assert _gather(ud, dtype=-1) == inv
+    assert _gather(ud, itype=2) == inv
+    assert _gather(ud, table=None) == inv
+    assert _gather(ud, idx=None) == inv
+    assert _gather(ud, out=None) == inv
+    assert _gather(ud, table=0x1002) == inv            # fp32 table must be 4-byte aligned
+    assert _gather(ud, table=0x1001, dtype=1) == inv   # fp16 table must be 2-byte aligned
+    assert _gather(ud, out=0x3002) == inv
+    assert _gather(ud, idx=0x2004) == inv              # int64 IDs must be 8-byte aligned
+    assert _gather(ud, N=2**40, D=2**30) == inv        # byte count overflows int64
+    assert _gather(ud, M=2**40, D=2**30, N=4) == inv
+
+
+def test_empty_gather_is_ok_without_a_device(ud):
+    assert _gather(ud, M=0, table=None, idx=None, out=None) == ud.UD_OK
+
+
+def test_tuning_fields_are_range_checked(ud):
+    T = ud.ud_tuning
+    inv = ud.UD_ERR_INVALID_ARG
+    assert _gather(ud, tuning=T(3, 0, 0, 0, 0)) == inv       # not a power of two
+    assert _gather(ud, tuning=T(128, 0, 0, 0, 0)) == inv
+    assert _gather(ud, tuning=T(0, 5, 0, 0, 0)) == inv
+    assert _gather(ud, tuning=T(0, 0, 3, 0, 0)) == inv
+    assert _gather(ud, tuning=T(0, 0, 0, -1, 0)) == inv
+    assert _gather(ud, tuning=T(0, 0, 0, 0, 8)) == inv
+    assert _gather(ud, tuning=T(0, 4, 8, 0, 0)) == ud.UD_ERR_UNSUPPORTED   # no such instantiation
+    assert _gather(ud, M=0, tuning=T(64, 2, 4, 0, 3)) == ud.UD_OK
+
+
+def test_table_calls_reject_bad_arguments(ud):
+    inv = ud.UD_ERR_INVALID_ARG
+    t = ctypes.c_void_p()
+    rs = ud.binding.raw_status
+    assert rs("ud_alloc_table", 0, 4, 0, 0, ctypes.byref(t)) == inv
+    assert rs("ud_alloc_table", 4, 0, 0, 0, ctypes.byref(t)) == inv
+    assert rs("ud_alloc_table", 4, 4, 2, 0, ctypes.byref(t)) == inv      # UD_F16_TO_F32 is not a storage type
+    assert rs("ud_alloc_table", 4, 4, 0, 2, ctypes.byref(t)) == inv      # unknown flag
+    assert rs("ud_alloc_table", 4, 4, 0, 0, None) == inv
+    assert rs("ud_alloc_table", 2**40, 2**30, 0, 0, ctypes.byref(t)) == inv
+    assert rs("ud_table_to_device", None, 0, 1, ctypes.byref(t)) == inv
+    assert rs("ud_table_host_ptr", None, ctypes.byref(t)) == inv
+    assert rs("ud_table_device_ptr", None, ctypes.byref(t)) == inv
+    assert rs("ud_table_shape", None, None, None, None) == inv
+    assert rs("ud_free_table", None) == ud.UD_OK                          # NULL is a no-op
+
+
+def test_plan_follows_row_width(ud):
+    for D, lanes, chunks in [(16, 4, 1), (64, 16, 1), (100, 32, 1), (128, 32, 1), (256, 64, 1), (602, 64, 3)]:
+        p = ud.ud_gather_plan(0x10000, D, ud.UD_F32)
+        assert (p.lanes_per_row, p.chunks_per_lane) == (lanes, chunks), D
+        assert p.rows_in_flight * p.chunks_per_lane <= 8
+    p = ud.ud_gather_plan(0x10000, 602, ud.UD_F16_TO_F32)
+    assert (p.lanes_per_row, p.chunks_per_lane) == (64, 2)

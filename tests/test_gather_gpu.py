@@ -1,0 +1,285 @@
+"""GPU parity: the HIP gather, called through the C ABI, against the CPU oracle.
+
+Bit-exact comparison (integer/bit work: the gather copies patterns, the
+widening is exact), on seeded inputs that span several wavefront batches and a
+ragged tail, for every kernel instantiation the library can select.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ud():
+    import paper_2101_07956_amd as m
+    return m
+
+
+CANARY = 0x5A
+
+
+def run_gather(ud, table, idx_np, dtype, tuning=None, out_offset_elems=0):
+    """Gather on the GPU into a canary-filled buffer; returns the (M, D) result as raw bits."""
+    M = idx_np.size
+    obytes = 2 if dtype == ud.UD_F16 else 4
+    pad = 64
+    total = M * table.D + out_offset_elems + pad
+    buf = torch.full((total * obytes,), CANARY, dtype=torch.uint8, device="cuda")
+    idx = torch.from_numpy(idx_np).cuda()
+    out_ptr = buf.data_ptr() + out_offset_elems * obytes
+    stream = torch.cuda.current_stream().cuda_stream
+    ud.ud_gather_tuned(table.device_ptr, table.N, table.D, dtype, idx.data_ptr(),
+                       ud.UD_I64 if idx_np.dtype == np.int64 else ud.UD_I32, M, out_ptr, stream, tuning)
+    ud.ud_gather_status(stream)
+    host = buf.cpu().numpy()
+    lo = out_offset_elems * obytes
+    hi = lo + M * table.D * obytes
+    assert (host[:lo] == CANARY).all(), "wrote before the output"
+    assert (host[hi:] == CANARY).all(), "wrote past the output"
+    return host[lo:hi].view(np.uint16 if obytes == 2 else np.uint32).reshape(M, table.D)
+
+
+def oracle_bits(table_np, idx_np, dtype):
+    o = oracle.gather(table_np, idx_np, dtype)
+    return o.view(np.uint16 if o.dtype.itemsize == 2 else np.uint32)
+
+
+def make_table(ud, N, D, elem, seed, flags=0):
+    t = ud.Table(N, D, elem, flags)
+    if elem == ud.UD_F32:
+        workloads.fill_uniform_f32(t.host_ptr, seed, N * D)
+    else:
+        workloads.fill_normal_f16(t.host_ptr, seed, N * D)
+    return t
+
+
+def test_config1_single_gather(ud):
+    # fp32 100,000 x 128, uniform[-1,1) seed 0; 16,384 int64 IDs uniform with replacement
+    t = make_table(ud, 100_000, 128, ud.UD_F32, 0)
+    idx = workloads.indices_uniform(workloads.IDX_STREAM, 16_384, 100_000)
+    got = run_gather(ud, t, idx, ud.UD_F32)
+    assert np.array_equal(got, oracle_bits(t.numpy(), idx, oracle.F32))
+    t.free()
+
+
+WIDTHS = [1, 2, 3, 4, 5, 7, 16, 25, 64, 100, 127, 128, 129, 255, 256, 257, 300, 602, 603, 1031]
+
+
+@pytest.mark.parametrize("D", WIDTHS)
+def test_f32_widths_default_plan(ud, D):
+    N, M = 3001, 2377                      # M is no multiple of any rows-per-wavefront
+    t = make_table(ud, N, D, ud.UD_F32, 100 + D)
+    for idt in (np.int64, np.int32):
+        idx = workloads.indices_uniform(7, M, N, idt)
+        idx[:3] = [0, N - 1, N - 1]        # first and last row, head and tail chunks at the table's ends
+        got = run_gather(ud, t, idx, ud.UD_F32, out_offset_elems=D % 4)
+        assert np.array_equal(got, oracle_bits(t.numpy(), idx, oracle.F32)), (D, idt)
+    t.free()
+
+
+@pytest.mark.parametrize("D", [1, 3, 8, 9, 100, 301, 602, 603, 1027])
+@pytest.mark.parametrize("dtype_name", ["UD_F16", "UD_F16_TO_F32"])
+def test_f16_widths_default_plan(ud, D, dtype_name):
+    dtype = getattr(ud, dtype_name)
+    N, M = 2503, 1999
+    t = make_table(ud, N, D, ud.UD_F16, 200 + D)
+    idx = workloads.indices_uniform(8, M, N, np.int32)
+    idx[:3] = [0, N - 1, N - 1]
+    got = run_gather(ud, t, idx, dtype, out_offset_elems=D % 3)
+    assert np.array_equal(got, oracle_bits(t.numpy(), idx, dtype)), D
+    t.free()
+
+
+PLANS = [(u, p) for u, p in itertools.product((1, 2, 4, 8), (1, 2, 3, 4)) if u * p <= 8]
+
+
+@pytest.mark.parametrize("u,p", PLANS)
+def test_every_instantiation_every_group_size(ud, u, p):
+    # each (rows in flight, chunks per lane) kernel with each lane-group size, with and
+    # without streaming hints, on a width whose rows start at 4 different offsets mod 16
+    N, M = 1201, 1103
+    cases = [(ud.UD_F32, ud.UD_F32, 77), (ud.UD_F16, ud.UD_F16_TO_F32, 301), (ud.UD_F16, ud.UD_F16, 75)]
+    for elem, dtype, D in cases:
+        t = make_table(ud, N, D, elem, 300 + D)
+        idx = workloads.indices_uniform(9, M, N)
+        want = oracle_bits(t.numpy(), idx, dtype)
+        for lanes in (1, 2, 4, 8, 16, 32, 64):
+            for flags in (0, ud.UD_TUNE_NT_LOAD | ud.UD_TUNE_NT_STORE):
+                tun = ud.ud_tuning(lanes, p, u, 0, flags)
+                got = run_gather(ud, t, idx, dtype, tun)
+                assert np.array_equal(got, want), (dtype, D, lanes, u, p, flags)
+        t.free()
+
+
+def test_grid_stride_when_blocks_are_capped(ud):
+    N, D, M = 5000, 100, 40_000
+    t = make_table(ud, N, D, ud.UD_F32, 5)
+    idx = workloads.indices_uniform(10, M, N)
+    want = oracle_bits(t.numpy(), idx, oracle.F32)
+    for blocks in (1, 7, 256):
+        got = run_gather(ud, t, idx, ud.UD_F32, ud.ud_tuning(0, 0, 0, blocks, 0))
+        assert np.array_equal(got, want), blocks
+    t.free()
+
+
+@pytest.mark.parametrize("dtype_name,elem_name,D", [("UD_F32", "UD_F32", 37), ("UD_F16_TO_F32", "UD_F16", 301),
+                                                     ("UD_F16", "UD_F16", 33)])
+def test_elementwise_kernel(ud, dtype_name, elem_name, D):
+    dtype, elem = getattr(ud, dtype_name), getattr(ud, elem_name)
+    N, M = 777, 1500
+    t = make_table(ud, N, D, elem, 6)
+    idx = workloads.indices_uniform(11, M, N, np.int32)
+    got = run_gather(ud, t, idx, dtype, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE))
+    assert np.array_equal(got, oracle_bits(t.numpy(), idx, dtype))
+    t.free()
+
+
+def test_index_patterns(ud):
+    N, D = 4099, 100
+    t = make_table(ud, N, D, ud.UD_F32, 12)
+    tab = t.numpy()
+    got = run_gather(ud, t, np.arange(N, dtype=np.int64), ud.UD_F32)
+    assert got.tobytes() == tab.tobytes()                       # arange is the identity
+    got = run_gather(ud, t, np.full(3000, 1234, dtype=np.int64), ud.UD_F32)
+    assert (got == tab[1234].view(np.uint32)).all()             # all-equal IDs
+    got = run_gather(ud, t, np.full(777, N - 1, dtype=np.int32), ud.UD_F32)
+    assert (got == tab[N - 1].view(np.uint32)).all()            # last row only
+    idx = workloads.indices_uniform(13, 5000, N)
+    perm = np.random.default_rng(0).permutation(idx.size)
+    a = run_gather(ud, t, idx, ud.UD_F32)
+    b = run_gather(ud, t, idx[perm], ud.UD_F32)
+    assert np.array_equal(a[perm], b)                           # permuting IDs permutes rows
+    t.free()
+
+
+def test_tag_table_closed_form(ud):
+    N, D = 70_001, 602
+    t = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_tag(t.host_ptr, N * D, 4)
+    idx = workloads.indices_uniform(14, 30_011, N)
+    got = run_gather(ud, t, idx, ud.UD_F32).astype(np.int64)
+    assert np.array_equal(got, idx[:, None] * D + np.arange(D)[None, :])
+    t.free()
+
+
+def test_all_65536_half_patterns_widen_exactly(ud):
+    t = ud.Table(256, 256, ud.UD_F16)
+    t.numpy().view(np.uint16)[:] = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(256, 256)
+    for idx in (np.arange(256, dtype=np.int64), np.random.default_rng(1).permutation(256).astype(np.int64)):
+        want = oracle_bits(t.numpy(), idx, oracle.F16_TO_F32)
+        assert np.array_equal(run_gather(ud, t, idx, ud.UD_F16_TO_F32), want)
+        assert np.array_equal(run_gather(ud, t, idx, ud.UD_F16_TO_F32, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE)), want)
+        assert np.array_equal(run_gather(ud, t, idx, ud.UD_F16), t.numpy().view(np.uint16)[idx])
+    t.free()
+
+
+def test_special_fp32_patterns_pass_unchanged(ud):
+    pats = np.array([0x7fc00001, 0xffc12345, 0x7f800001, 0x80000000, 0x00000001, 0x7f800000, 0xff800000, 0x807fffff,
+                     0x00000000, 0xffffffff], dtype=np.uint32)
+    t = ud.Table(64, 10, ud.UD_F32)
+    t.numpy().view(np.uint32)[:] = np.stack([np.roll(pats, k) for k in range(64)])
+    idx = workloads.indices_uniform(15, 500, 64)
+    assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32), t.numpy().view(np.uint32)[idx])
+    t.free()
+
+
+@pytest.mark.parametrize("shift_elems", [1, 2, 3])
+def test_table_base_not_16_byte_aligned(ud, shift_elems):
+    # a raw table pointer that is only element-aligned: rows of a larger allocation, offset by a few elements
+    N, D = 1000, 37
+    big = ud.Table(N + 1, D, ud.UD_F32)
+    workloads.fill_uniform_f32(big.host_ptr, 16, (N + 1) * D)
+    flat = big.numpy().ravel()
+    view = flat[shift_elems:shift_elems + N * D].reshape(N, D)
+    idx = workloads.indices_uniform(17, 1500, N)
+    idx[:2] = [0, N - 1]
+    M = idx.size
+    out = torch.full((M * D + 16,), -1, dtype=torch.int32, device="cuda")
+    didx = torch.from_numpy(idx).cuda()
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_gather(big.device_ptr + 4 * shift_elems, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, out.data_ptr(), s)
+    ud.ud_gather_status(s)
+    host = out.cpu().numpy()
+    assert (host[M * D:] == -1).all()
+    assert np.array_equal(host[:M * D].view(np.uint32).reshape(M, D), oracle_bits(np.ascontiguousarray(view), idx, oracle.F32))
+    big.free()
+
+
+def test_noncoherent_host_table_and_device_resident_table(ud):
+    N, D, M = 20_000, 256, 9001
+    for flags in (ud.UD_TABLE_COHERENT, ud.UD_TABLE_NONCOHERENT):
+        t = make_table(ud, N, D, ud.UD_F32, 18, flags)
+        idx = workloads.indices_uniform(19, M, N)
+        want = oracle_bits(t.numpy(), idx, oracle.F32)
+        assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32), want)
+        dev = t.to_device()
+        assert dev.host_ptr == 0 and dev.N == N and dev.D == D
+        assert np.array_equal(run_gather(ud, dev, idx, ud.UD_F32), want)
+        # a slice of rows held in HBM: IDs are relative to the slice
+        part = t.to_device(5000, 4000)
+        idx2 = workloads.indices_uniform(20, 3000, 4000)
+        assert np.array_equal(run_gather(ud, part, idx2, ud.UD_F32), oracle_bits(t.numpy()[5000:9000], idx2, oracle.F32))
+        for x in (part, dev, t):
+            x.free()
+
+
+def test_empty_id_list_is_a_no_op(ud):
+    t = make_table(ud, 10, 8, ud.UD_F32, 21)
+    out = torch.full((8,), 7, dtype=torch.int32, device="cuda")
+    ud.ud_gather(t.device_ptr, 10, 8, ud.UD_F32, None, ud.UD_I64, 0, out.data_ptr(), None)
+    ud.ud_gather_status(None)
+    assert (out.cpu().numpy() == 7).all()
+    t.free()
+
+
+@pytest.mark.parametrize("idt", [np.int64, np.int32])
+@pytest.mark.parametrize("elementwise", [False, True])
+def test_out_of_range_ids_are_reported_and_never_dereferenced(ud, idt, elementwise):
+    N, D, M = 500, 100, 4000
+    t = make_table(ud, N, D, ud.UD_F32, 22)
+    tun = ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE if elementwise else 0)
+    idx = workloads.indices_uniform(23, M, N, idt)
+    for bad_positions, bad_values in (([3111, 1717, 2500], [N, -1, N + 5]), ([0], [-7]), ([M - 1], [2**31 - 1])):
+        bad = idx.copy()
+        bad[bad_positions] = bad_values
+        with pytest.raises(ud.UdIndexError) as e:
+            run_gather(ud, t, bad, ud.UD_F32, tun)
+        assert e.value.pos == min(bad_positions)
+        with pytest.raises(oracle.OracleIndexError) as oe:          # the oracle reports the same position
+            oracle.gather(t.numpy(), bad)
+        assert oe.value.pos == e.value.pos
+        # the record is cleared by the status call: a clean gather afterwards passes
+        assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32, tun), oracle_bits(t.numpy(), idx, oracle.F32))
+    if idt == np.int64:
+        bad = idx.copy()
+        bad[10] = 2**32 + 3                                          # would alias row 3 if truncated to 32 bits
+        with pytest.raises(ud.UdIndexError) as e:
+            run_gather(ud, t, bad, ud.UD_F32, tun)
+        assert e.value.pos == 10
+    t.free()
+
+
+def test_rows_with_valid_ids_are_still_gathered_when_another_id_is_bad(ud):
+    N, D, M = 300, 64, 1000
+    t = make_table(ud, N, D, ud.UD_F32, 24)
+    idx = workloads.indices_uniform(25, M, N)
+    idx[500] = N
+    out = torch.zeros((M, D), dtype=torch.float32, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, torch.from_numpy(idx).cuda().data_ptr(), ud.UD_I64, M, out.data_ptr(), s)
+    with pytest.raises(ud.UdIndexError):
+        ud.ud_gather_status(s)
+    host = out.cpu().numpy()
+    good = np.ones(M, dtype=bool)
+    good[500] = False
+    assert np.array_equal(host[good], t.numpy()[idx[good]])
+    assert (host[500] == 0).all()                                    # the bad row is left unwritten
+    t.free()
