@@ -4,6 +4,7 @@
 memory (or in HBM), read directly by GPU wavefronts -- the hot path of
 PyTorch-Direct (arXiv 2101.07956, Sections 3 and 4.5).  The work is done by
 ``libud.so`` (C ABI in ``include/ud.h``); this package is its thin binding.
+Importing it fails loudly if the library has not been built.
 """
 from .binding import *  # noqa: F401,F403
 from .binding import EXPORTS, LIB_PATH, UdError, UdIndexError, ud_tuning  # noqa: F401

@@ -10,7 +10,10 @@
 //    pinned-host -> device hipMemcpy rate (the host link's practical peak) and a
 //    device -> device copy rate.
 //
-// Host code only; shares nothing with the gather kernels.
+//  * udb_plain_copy: a plain streaming copy kernel of known size, the reference
+//    against which hardware byte counters are scaled when profiling.
+//
+// Shares nothing with the gather kernels.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -59,9 +62,32 @@ void cpu_gather_rows(const char *table, int64_t row_bytes, const int64_t *idx, i
         th.join();
 }
 
+// dst[k] = src[k] for n 16-byte words, grid-stride
+__global__ __launch_bounds__(256) void plain_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t k = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; k < n; k += stride)
+        dst[k] = src[k];
+}
+
 } // namespace
 
 extern "C" {
+
+// Enqueue a copy of `bytes` bytes (a multiple of 16; both pointers 16-byte
+// aligned device pointers) on `stream`: reads `bytes`, writes `bytes`.
+int udb_plain_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (bytes % 16 || !dst || !src)
+        return 1;
+    const size_t n = bytes / 16;
+    if (n == 0)
+        return 0;
+    const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n + 255) / 256, 256 * 32));
+    hipLaunchKernelGGL(plain_copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
 
 // Best and median rate (GB/s, 1e9 bytes) of `reps` synchronous pinned-host ->
 // device copies of `bytes` bytes.  Allocates and frees its own buffers.

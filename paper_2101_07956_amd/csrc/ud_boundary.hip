@@ -96,22 +96,52 @@ int64_t max_chunks_per_row(uintptr_t base, int64_t row_bytes)
 
 constexpr int kDefaultMaxBlocks = 1 << 22;
 
+// Where does the table live?  The two cases are bound by different things (the
+// host link, or HBM) and want different launch shapes.  Asked of the runtime
+// once per pointer and remembered per thread; an unknown pointer is treated as
+// host memory (this only steers tuning, never correctness).
+bool table_is_in_hbm(const void *table)
+{
+    thread_local const void *last_ptr = nullptr;
+    thread_local bool last_kind = false;
+    if (table && table == last_ptr)
+        return last_kind;
+    hipPointerAttribute_t attr{};
+    bool in_hbm = false;
+    if (hipPointerGetAttributes(&attr, table) == hipSuccess)
+        in_hbm = attr.type == hipMemoryTypeDevice;
+    else
+        (void)hipGetLastError();
+    last_ptr = table;
+    last_kind = in_hbm;
+    return in_hbm;
+}
+
+// Launch shape by row width and table residence, from sweeps on MI355X:
+//  * host table (link-bound): one row per wavefront instruction (64 lanes per
+//    row) as soon as a row spans at least two 128-byte lines, a single row in
+//    flight per lane group, as many workgroups as there are rows.  Whole-wave
+//    loads of one row reach 99-100% of the pinned-memcpy rate for 256..1024-byte
+//    rows; packing several short rows into one instruction costs 3-5%.
+//  * HBM table (bandwidth-bound): no idle lanes (lanes per row = chunks per row
+//    rounded up to a power of two), two rows in flight, streaming stores.
 ud::Plan auto_plan(const void *table, int64_t D, ud_dtype dtype)
 {
     const int64_t row_bytes = D * elem_bytes(dtype);
     const int64_t nch = max_chunks_per_row(reinterpret_cast<uintptr_t>(table), row_bytes);
+    const bool hbm = table_is_in_hbm(table);
     ud::Plan p{};
-    p.flags = 0;
+    p.flags = hbm ? UD_TUNE_NT_STORE : 0u;
     p.max_blocks = kDefaultMaxBlocks;
     if (nch <= 64) {
-        p.lanes_per_row = next_pow2(nch);
+        p.lanes_per_row = (!hbm && row_bytes >= 256) ? 64 : next_pow2(nch);
         p.chunks_per_lane = 1;
-        p.rows_in_flight = 8;
+        p.rows_in_flight = hbm ? 2 : 1;
     } else {
         p.lanes_per_row = 64;
         const int64_t passes = (nch + 63) / 64;
         p.chunks_per_lane = passes > 4 ? 4 : static_cast<int>(passes);
-        p.rows_in_flight = p.chunks_per_lane == 2 ? 4 : 2;
+        p.rows_in_flight = (hbm && p.chunks_per_lane <= 2) ? 2 : 1;
     }
     return p;
 }
@@ -266,7 +296,7 @@ ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtyp
         if (tuning->rows_in_flight)
             plan.rows_in_flight = tuning->rows_in_flight;
         else if (tuning->chunks_per_lane && plan.rows_in_flight * plan.chunks_per_lane > 8)
-            plan.rows_in_flight = plan.chunks_per_lane >= 3 ? 2 : 4;
+            plan.rows_in_flight = 1;
         if (tuning->max_blocks)
             plan.max_blocks = tuning->max_blocks;
         if (plan.rows_in_flight * plan.chunks_per_lane > 8)

@@ -93,9 +93,15 @@ def test_table_calls_reject_bad_arguments(ud):
 
 
 def test_plan_follows_row_width(ud):
-    for D, lanes, chunks in [(16, 4, 1), (64, 16, 1), (100, 32, 1), (128, 32, 1), (256, 64, 1), (602, 64, 3)]:
+    # an address the runtime does not know counts as host memory: one row per wavefront
+    # instruction from 256-byte rows up, natural group size below
+    for D, lanes, chunks in [(16, 4, 1), (32, 8, 1), (64, 64, 1), (100, 64, 1), (128, 64, 1), (256, 64, 1),
+                             (602, 64, 3), (4096, 64, 4)]:
         p = ud.ud_gather_plan(0x10000, D, ud.UD_F32)
         assert (p.lanes_per_row, p.chunks_per_lane) == (lanes, chunks), D
         assert p.rows_in_flight * p.chunks_per_lane <= 8
     p = ud.ud_gather_plan(0x10000, 602, ud.UD_F16_TO_F32)
+    assert (p.lanes_per_row, p.chunks_per_lane) == (64, 2)
+    # rows that start at 4 different offsets modulo 16 can overlap one more chunk
+    p = ud.ud_gather_plan(0x10000, 255, ud.UD_F32)      # 1020-byte rows: up to 65 chunks
     assert (p.lanes_per_row, p.chunks_per_lane) == (64, 2)

@@ -283,3 +283,14 @@ def test_rows_with_valid_ids_are_still_gathered_when_another_id_is_bad(ud):
     assert np.array_equal(host[good], t.numpy()[idx[good]])
     assert (host[500] == 0).all()                                    # the bad row is left unwritten
     t.free()
+
+
+def test_plan_depends_on_where_the_table_lives(ud):
+    t = make_table(ud, 5000, 128, ud.UD_F32, 26)
+    host_plan = ud.ud_gather_plan(t.device_ptr, 128, ud.UD_F32)
+    assert host_plan.lanes_per_row == 64 and host_plan.rows_in_flight == 1 and host_plan.flags == 0
+    d = t.to_device()
+    dev_plan = ud.ud_gather_plan(d.device_ptr, 128, ud.UD_F32)
+    assert dev_plan.lanes_per_row == 32 and dev_plan.rows_in_flight == 2 and dev_plan.flags == ud.UD_TUNE_NT_STORE
+    d.free()
+    t.free()
