@@ -52,7 +52,8 @@ def _load_baseline_lib(ud):
 
 
 def _read_traffic_note():
-    """HBM/link traffic per launch of the dominant kernel, from the committed rocprofv3 counter summary."""
+    """Fabric traffic (bytes per launch) of the dominant kernel, measured offline with rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE and kept in the committed counter summary; None if that file is absent."""
     path = os.path.join(ROOT, "profiles", "gather_f32_D602_traffic.txt")
     if not os.path.exists(path):
         return None
@@ -239,6 +240,9 @@ def main() -> int:
         "roofline": {"bound": "host_link", "kernel": "gather_chunked<f32> D=602 (2408-byte rows)",
                      "achieved": round(dom_achieved, 2), "peak": round(h2d_peak, 2), "unit": "GB/s",
                      "frac": round(dom_achieved / h2d_peak, 4), "traffic": traffic,
+                     "traffic_unit": "bytes per launch (L2<->fabric reads + writes, rocprofv3 FETCH_SIZE/WRITE_SIZE)",
+                     "algorithmic_bytes_per_launch": M_ROWS * (2 * 602 * 4 + 8),
+                     "link_bytes_per_launch": M_ROWS * 602 * 4,
                      "peak_source": "best of 10 pinned hipMemcpy H2D of 1 GiB in this run",
                      "ms_per_launch": round(dom_ms, 4)},
         "roofline_hbm": {"bound": "hbm", "kernel": "gather_chunked<f32> D=602, table in HBM",

@@ -120,9 +120,11 @@ bool table_is_in_hbm(const void *table)
 // Launch shape by row width and table residence, from sweeps on MI355X:
 //  * host table (link-bound): one row per wavefront instruction (64 lanes per
 //    row) as soon as a row spans at least two 128-byte lines, a single row in
-//    flight per lane group, as many workgroups as there are rows.  Whole-wave
-//    loads of one row reach 99-100% of the pinned-memcpy rate for 256..1024-byte
-//    rows; packing several short rows into one instruction costs 3-5%.
+//    flight per lane group.  Whole-wave loads of one row reach 99-100% of the
+//    pinned-memcpy rate for 256..1024-byte rows; packing several short rows
+//    into one instruction costs 3-5%.  From 1 KiB rows up a fixed grid of 512
+//    workgroups striding over the rows is 1-3% faster than one wavefront per
+//    row; below that, one wavefront batch per workgroup slot is best.
 //  * HBM table (bandwidth-bound): no idle lanes (lanes per row = chunks per row
 //    rounded up to a power of two), two rows in flight, streaming stores.
 ud::Plan auto_plan(const void *table, int64_t D, ud_dtype dtype)
@@ -143,6 +145,8 @@ ud::Plan auto_plan(const void *table, int64_t D, ud_dtype dtype)
         p.chunks_per_lane = passes > 4 ? 4 : static_cast<int>(passes);
         p.rows_in_flight = (hbm && p.chunks_per_lane <= 2) ? 2 : 1;
     }
+    if (!hbm && row_bytes >= 1024)
+        p.max_blocks = 512;
     return p;
 }
 
