@@ -55,6 +55,20 @@ def lib():
         for name in ("wl_indices_uniform_i64", "wl_indices_uniform_i32"):
             getattr(L, name).restype = None
             getattr(L, name).argtypes = [_vp, _u64, _u64, _u64]
+        _i64 = ctypes.c_int64
+        _dbl = ctypes.c_double
+        L.wl_node_of_rank.restype = _i64
+        L.wl_node_of_rank.argtypes = [_u64, _u64, _u64]
+        L.wl_zipf_rank.restype = _u64
+        L.wl_zipf_rank.argtypes = [_u64, _u64, _u64, _dbl]
+        L.wl_graph_degrees.restype = _i64
+        L.wl_graph_degrees.argtypes = [_vp, _u64, _dbl, _i64, _u64]
+        L.wl_graph_fill_ids.restype = None
+        L.wl_graph_fill_ids.argtypes = [_vp, _vp, _u64, _dbl, _u64]
+        L.wl_sample_csr.restype = _i64
+        L.wl_sample_csr.argtypes = [_vp, _vp, _u64, _i64, _vp, ctypes.c_int, _u64, _u64, _vp, _i64]
+        L.wl_sample_procedural.restype = _i64
+        L.wl_sample_procedural.argtypes = [_u64, _i64, _dbl, _u64, _i64, _vp, ctypes.c_int, _u64, _u64, _vp, _i64]
         _lib = L
     return _lib
 
@@ -111,3 +125,55 @@ def indices_uniform(seed: int, M: int, N: int, dtype=np.int64) -> np.ndarray:
 
 #: seed stream used for ID lists, kept apart from the table's value stream
 IDX_STREAM = 0x1D5
+
+
+# ---- power-law graphs and minibatch neighbour sampling (see graph.c) ----
+
+def zipf_graph_csr(N: int, mean_degree: float, dmin: int, alpha: float, seed: int):
+    """CSR (int64 offsets[N+1], int64 ids[E]) of a Zipf(1.0)-degree graph with degree floor ``dmin``
+    and neighbour popularity ~ rank**-alpha."""
+    deg = np.empty(N, dtype=np.int64)
+    total = lib().wl_graph_degrees(deg.ctypes.data, N, float(mean_degree), dmin, seed)
+    offsets = np.zeros(N + 1, dtype=np.int64)
+    np.cumsum(deg, out=offsets[1:])
+    assert offsets[-1] == total
+    ids = np.empty(total, dtype=np.int64)
+    lib().wl_graph_fill_ids(offsets.ctypes.data, ids.ctypes.data, N, float(alpha), seed)
+    return offsets, ids
+
+
+def slot_bound(nseeds: int, fanout) -> int:
+    n = nseeds
+    for f in fanout:
+        n *= 1 + f
+    return n
+
+
+def sample_csr(offsets: np.ndarray, ids: np.ndarray, nseeds: int, fanout, seed: int, batch: int) -> np.ndarray:
+    """Distinct node IDs of one minibatch, first-occurrence order, seeds first."""
+    fan = np.asarray(fanout, dtype=np.int64)
+    cap = slot_bound(nseeds, fanout)
+    out = np.empty(cap, dtype=np.int64)
+    n = lib().wl_sample_csr(offsets.ctypes.data, ids.ctypes.data, offsets.size - 1, nseeds, fan.ctypes.data,
+                            fan.size, seed, batch, out.ctypes.data, cap)
+    if n < 0:
+        raise MemoryError("wl_sample_csr failed")
+    return out[:n].copy()
+
+
+def sample_procedural(N: int, degree: int, alpha: float, graph_seed: int, nseeds: int, fanout, seed: int,
+                      batch: int) -> np.ndarray:
+    """Same for the never-materialised graph in which every node has ``degree`` hashed neighbour slots."""
+    fan = np.asarray(fanout, dtype=np.int64)
+    cap = slot_bound(nseeds, fanout)
+    out = np.empty(cap, dtype=np.int64)
+    n = lib().wl_sample_procedural(N, degree, float(alpha), graph_seed, nseeds, fan.ctypes.data, fan.size, seed,
+                                   batch, out.ctypes.data, cap)
+    if n < 0:
+        raise MemoryError("wl_sample_procedural failed")
+    return out[:n].copy()
+
+
+#: the two GraphSAGE-style workloads: graph and sampling parameters (see DESIGN.md for why alpha differs)
+PRODUCTS_LIKE = dict(N=2_400_000, D=100, mean_degree=50, dmin=25, alpha=0.6, nseeds=1024, fanout=(25, 10))
+PAPERS_LIKE = dict(N=111_000_000, D=256, degree=30, alpha=0.8, nseeds=1024, fanout=(15, 10, 5))
