@@ -63,6 +63,280 @@ def _read_traffic_note():
     return None
 
 
+def _stats(ms):
+    ms = sorted(ms)
+    return {"median_ms": round(ms[len(ms) // 2], 4), "min_ms": round(ms[0], 4), "reps": len(ms)}
+
+
+def _itype(ud, t):
+    import torch
+    return ud.UD_I64 if t.dtype == torch.int64 else ud.UD_I32
+
+
+def _kernel_times(ud, torch, tptr, N, D, dtype, id_tensors, out, warm, tuning=None):
+    """Kernel-only time (HIP events on the launch stream) of one gather per ID tensor; the first `warm` are untimed."""
+    stream = torch.cuda.current_stream().cuda_stream
+    ev = []
+    for k, ids in enumerate(id_tensors):
+        if k >= warm:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        ud.ud_gather_tuned(tptr, N, D, dtype, ids.data_ptr(), _itype(ud, ids), ids.numel(), out.data_ptr(), stream, tuning)
+        if k >= warm:
+            e1.record()
+            ev.append((e0, e1))
+    torch.cuda.synchronize()
+    ud.ud_gather_status(stream)
+    return [a.elapsed_time(b) for a, b in ev]
+
+
+def _wall_times(ud, torch, tptr, N, D, dtype, ids_pinned, out, warm):
+    """Call-to-sync wall time per gather INCLUDING the host->device copy of the ID list (pinned source)."""
+    stream = torch.cuda.current_stream()
+    dst = torch.empty(max(t.numel() for t in ids_pinned), dtype=ids_pinned[0].dtype, device="cuda")
+    ms = []
+    for k, ids in enumerate(ids_pinned):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        d = dst[: ids.numel()]
+        d.copy_(ids, non_blocking=True)
+        ud.ud_gather(tptr, N, D, dtype, d.data_ptr(), _itype(ud, d), ids.numel(), out.data_ptr(), stream.cuda_stream)
+        stream.synchronize()
+        if k >= warm:
+            ms.append((time.perf_counter() - t0) * 1e3)
+    ud.ud_gather_status(stream.cuda_stream)
+    return ms
+
+
+def _cpu_centric(bl, ctx, table_host_ptr, row_bytes, ids_np, out_ptr, threads, slices=1):
+    a, b, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    rc = bl.udb_cpu_centric_gather(ctx, table_host_ptr, row_bytes, ids_np.ctypes.data, ids_np.size, out_ptr,
+                                   threads, slices, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if rc != 0:
+        raise RuntimeError(f"cpu-centric baseline failed ({rc})")
+    return a.value * 1e3
+
+
+def _h2d_rate(bl, nbytes, reps=10):
+    best, med = ctypes.c_double(), ctypes.c_double()
+    if bl.udb_h2d_peak(max(int(nbytes), 4096), reps, ctypes.byref(best), ctypes.byref(med)) != 0:
+        raise RuntimeError("hipMemcpy rate measurement failed")
+    return best.value
+
+
+def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
+    """The other configurations and the paper's two microbenchmark experiments (not the default bench line)."""
+    import oracle
+
+    K, W = args.steps, args.warmup
+    h2d_peak = _h2d_rate(bl, 1 << 30)
+    dev = torch.device("cuda:0")
+    wl = args.workload
+    res = {"metric": "zero_copy_gather_GBps", "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic",
+           "h2d_peak_GBps": round(h2d_peak, 2), "host": {"cores_visible": ncores, "device": torch.cuda.get_device_name(0)}}
+
+    def pinned(a):
+        return torch.from_numpy(a).pin_memory()
+
+    def finish(value, ms_per_step, dtype, config, **more):
+        res.update({"value": round(value, 3), "ms_per_step": round(ms_per_step, 4), "dtype": dtype, "config": config,
+                    "frac_of_h2d_peak": round(value / h2d_peak, 4)})
+        res.update(more)
+        print(json.dumps(res))
+        return 0
+
+    def spot_check(table, N, D, odtype, ids_np, out, n=2048):
+        sample = np.sort(np.random.default_rng(0).choice(ids_np.size, min(n, ids_np.size), replace=False))
+        got = out[: ids_np.size * D].view(ids_np.size, D)[torch.from_numpy(sample).to(dev)].cpu().numpy()
+        want = np.empty((sample.size, D), dtype=np.uint32)
+        oracle.gather_raw(table.host_ptr, N, D, odtype, np.ascontiguousarray(ids_np[sample]), want)
+        return bool(np.array_equal(got.view(np.uint32), want))
+
+    if wl == "single":
+        N, D, M = 100_000, 128, 16_384
+        table = ud.Table(N, D, ud.UD_F32)
+        workloads.fill_uniform_f32(table.host_ptr, 0, N * D)
+        ids_np = [workloads.indices_uniform(workloads.IDX_STREAM + k, M, N) for k in range(K + W)]
+        ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+        out = torch.empty(M * D, dtype=torch.float32, device=dev)
+        kern = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev, out, W)
+        ok = spot_check(table, N, D, oracle.F32, ids_np[-1], out)
+        wall = _wall_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, [pinned(a) for a in ids_np], out, W)
+        nbytes = M * D * 4
+        same_size = _h2d_rate(bl, nbytes, 20)
+        ks, ws = _stats(kern), _stats(wall)
+        return finish(nbytes / ks["median_ms"] / 1e6, ks["median_ms"], "f32",
+                      {"workload": "single gather: host-pinned fp32 100,000 x 128 (seed 0), 16,384 int64 IDs uniform with replacement"},
+                      kernel_only=ks, call_to_sync_incl_id_copy=ws, wall_GBps=round(nbytes / ws["median_ms"] / 1e6, 2),
+                      same_size_hipMemcpy_GBps=round(same_size, 2),
+                      frac_of_same_size_hipMemcpy=round(nbytes / ks["median_ms"] / 1e6 / same_size, 4),
+                      rows_per_s=round(M / ks["median_ms"] * 1e3), parity_spot_check=ok)
+
+    if wl == "graphsage":
+        p = workloads.PRODUCTS_LIKE
+        N, D = p["N"], p["D"]
+        table = ud.Table(N, D, ud.UD_F32)
+        workloads.fill_uniform_f32(table.host_ptr, 3, N * D)
+        offsets, nbr = workloads.zipf_graph_csr(N, p["mean_degree"], p["dmin"], p["alpha"], 3)
+        nb = 100
+        ids_np = [workloads.sample_csr(offsets, nbr, p["nseeds"], p["fanout"], 33, b) for b in range(nb)]
+        del offsets, nbr
+        ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+        cap = max(a.size for a in ids_np)
+        out = torch.empty(cap * D, dtype=torch.float32, device=dev)
+        kern = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev[:W] + ids_dev, out, W)
+        ok = spot_check(table, N, D, oracle.F32, ids_np[-1], out)
+        padded = [pinned(a) for a in ids_np]
+        wall = _wall_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, padded[:W] + padded, out, W)
+        total_bytes = sum(a.size for a in ids_np) * D * 4
+        extra = {}
+        if not args.no_cpu:
+            ctx = ctypes.c_void_p()
+            bl.udb_cpu_centric_create(cap * D * 4, ctypes.byref(ctx))
+            for name, th, sl in (("plain", threads, 1), ("double_buffered", threads, 4)):
+                _cpu_centric(bl, ctx, table.host_ptr, D * 4, ids_np[0], out.data_ptr(), th, sl)
+                ms = [_cpu_centric(bl, ctx, table.host_ptr, D * 4, a, out.data_ptr(), th, sl) for a in ids_np[:20]]
+                extra[name] = {"GBps": round(sum(a.size for a in ids_np[:20]) * D * 4 / sum(ms) / 1e6, 2), "threads": th}
+            bl.udb_cpu_centric_destroy(ctx)
+        sizes = [a.size for a in ids_np]
+        return finish(total_bytes / sum(kern) / 1e6, sum(kern) / nb, "f32",
+                      {"workload": "GraphSAGE-style minibatch gather: 2,400,000 x 100 fp32 host-pinned table, Zipf power-law "
+                                   "CSR graph (mean degree 50), 1,024 seeds, fanout [25,10], de-duplicated; 100 batches; one step = one batch",
+                       "unique_ids_per_batch": [min(sizes), max(sizes)]},
+                      kernel_only=_stats(kern), call_to_sync_incl_id_copy=_stats(wall),
+                      wall_GBps=round(total_bytes / sum(wall) / 1e6, 2), rows_per_s=round(sum(sizes) / sum(kern) * 1e3),
+                      cpu_centric=extra or None, parity_spot_check=ok)
+
+    if wl == "large":
+        p = workloads.PAPERS_LIKE
+        N, D = 62_500_000, p["D"]       # the largest table the box can pin (111,000,000 rows = 105.9 GiB is refused)
+        table = ud.Table(N, D, ud.UD_F32)
+        workloads.fill_uniform_f32(table.host_ptr, 4, N * D)
+        nb = max(K, 5)
+        ids_np = [workloads.sample_procedural(N, p["degree"], p["alpha"], 4, p["nseeds"], p["fanout"], 44, b) for b in range(nb)]
+        ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+        cap = max(a.size for a in ids_np)
+        out = torch.empty(cap * D, dtype=torch.float32, device=dev)
+        kern = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev[:W] + ids_dev, out, W)
+        ok = spot_check(table, N, D, oracle.F32, ids_np[-1], out)
+        total_bytes = sum(a.size for a in ids_np) * D * 4
+        # device-resident variant on a 16,000,000-row slice: IDs folded into the slice, de-duplicated again
+        srows = 16_000_000
+        devt = table.to_device(0, srows)
+        folded = []
+        for a in ids_np:
+            f = a % srows
+            _, first = np.unique(f, return_index=True)
+            folded.append(np.ascontiguousarray(f[np.sort(first)]))
+        fdev = [torch.from_numpy(a).to(dev) for a in folded]
+        kern_h = _kernel_times(ud, torch, devt.device_ptr, srows, D, ud.UD_F32, fdev[:W] + fdev, out, W)
+        hbm_bytes = sum(a.size for a in folded) * (2 * D * 4 + 8)
+        devt.free()
+        sizes = [a.size for a in ids_np]
+        return finish(total_bytes / sum(kern) / 1e6, sum(kern) / nb, "f32",
+                      {"workload": "large host-resident table: 62,500,000 x 256 fp32 (64 GB pinned; the named 111,000,000 rows "
+                                   "exceed what hipHostMalloc grants on this box), procedural Zipf graph, 1,024 seeds, fanout "
+                                   "[15,10,5], de-duplicated; one step = one batch", "unique_ids_per_batch": [min(sizes), max(sizes)]},
+                      kernel_only=_stats(kern), rows_per_s=round(sum(sizes) / sum(kern) * 1e3),
+                      device_resident_slice={"rows": srows, "GBps_read_plus_write": round(hbm_bytes / sum(kern_h) / 1e6, 1),
+                                             "frac_of_8TBps": round(hbm_bytes / sum(kern_h) / 1e6 / HBM_PEAK_GBPS, 4),
+                                             "kernel_only": _stats(kern_h)},
+                      parity_spot_check=ok)
+
+    if wl == "fp16":
+        N, D, M = 10_000_000, 602, 2_000_000
+        table = ud.Table(N, D, ud.UD_F16)
+        workloads.fill_normal_f16(table.host_ptr, 5, N * D)
+        ids_np = [workloads.indices_uniform(workloads.IDX_STREAM + k, M, N, np.int32) for k in range(min(K, 10) + W)]
+        ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+        out = torch.empty(M * D, dtype=torch.float32, device=dev)
+        kern = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F16_TO_F32, ids_dev, out, W)
+        ok = spot_check(table, N, D, oracle.F16_TO_F32, ids_np[-1], out)
+        ks = _stats(kern)
+        link_bytes = M * D * 2
+        return finish(link_bytes / ks["median_ms"] / 1e6, ks["median_ms"], "f16->f32",
+                      {"workload": "half-precision odd-width table: host-pinned fp16 10,000,000 x 602 (N(0,1) rounded to fp16), "
+                                   "2,000,000 int32 IDs uniform, fused upcast to fp32 in HBM"},
+                      kernel_only=ks, hbm_write_GBps=round(2 * link_bytes / ks["median_ms"] / 1e6, 2),
+                      rows_per_s=round(M / ks["median_ms"] * 1e3), parity_spot_check=ok)
+
+    if wl == "align":
+        # Section 5.3 / Figure 7 of the paper: row sizes 2048..2076 bytes in 4-byte steps
+        N, M = 4_000_000, 262_144
+        widths = list(range(512, 520))
+        dmax = widths[-1]
+        table = ud.Table(N, dmax, ud.UD_F32)
+        workloads.fill_uniform_f32(table.host_ptr, 7, N * dmax)
+        reps = max(K, 5)
+        ids_np = [workloads.indices_uniform(workloads.IDX_STREAM + k, M, N) for k in range(reps + W)]
+        ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+        out = torch.empty(M * dmax, dtype=torch.float32, device=dev)
+        ctx = ctypes.c_void_p()
+        bl.udb_cpu_centric_create(M * dmax * 4, ctypes.byref(ctx))
+        naive = ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE)
+        rows, ok = {}, True
+        for D in widths:
+            nbytes = M * D * 4
+            opt = _stats(_kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev, out, W))
+            ok = ok and spot_check(table, N, D, oracle.F32, ids_np[-1], out)
+            nv = _stats(_kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev, out, W, naive))
+            _cpu_centric(bl, ctx, table.host_ptr, D * 4, ids_np[0], out.data_ptr(), threads)
+            py = sorted(_cpu_centric(bl, ctx, table.host_ptr, D * 4, a, out.data_ptr(), threads) for a in ids_np[1:6])[2]
+            rows[str(D * 4)] = {"zero_copy_ms": opt["median_ms"], "zero_copy_GBps": round(nbytes / opt["median_ms"] / 1e6, 2),
+                                "one_lane_per_element_ms": nv["median_ms"],
+                                "one_lane_per_element_GBps": round(nbytes / nv["median_ms"] / 1e6, 2),
+                                "cpu_centric_ms": round(py, 4), "ideal_ms": round(nbytes / h2d_peak / 1e6, 4),
+                                "speedup_vs_cpu_centric": round(py / opt["median_ms"], 3),
+                                "one_lane_per_element_speedup_vs_cpu_centric": round(py / nv["median_ms"], 3)}
+        bl.udb_cpu_centric_destroy(ctx)
+        tot_b = sum(M * D * 4 for D in widths)
+        tot_ms = sum(r["zero_copy_ms"] for r in rows.values())
+        return finish(tot_b / tot_ms / 1e6, tot_ms, "f32",
+                      {"workload": "alignment sweep: host-pinned fp32 table 4,000,000 rows, row bytes 2048..2076 step 4, "
+                                   "262,144 int64 IDs uniform; one step = one gather per row size", "cpu_centric_threads": threads},
+                      per_row_bytes=rows, parity_spot_check=ok)
+
+    if wl == "grid":
+        # Section 5.2 / Figure 6 of the paper: (rows copied, row bytes) from (8K, 256B) to (256K, 16KB)
+        region = 16 << 30
+        table = ud.Table(region // 16384, 4096, ud.UD_F32)      # 16 GiB, viewed with each row size
+        workloads.fill_uniform_f32(table.host_ptr, 6, region // 4)
+        reps = max(K, 5)
+        ctx = ctypes.c_void_p()
+        bl.udb_cpu_centric_create(262_144 * 16384, ctypes.byref(ctx))
+        out = torch.empty(262_144 * 4096, dtype=torch.float32, device=dev)
+        cells, ok = {}, True
+        tot_b = tot_ms = 0.0
+        for rb in (256, 1024, 4096, 16384):
+            D, N = rb // 4, region // rb
+            for M in (8_192, 32_768, 131_072, 262_144):
+                ids_np = [workloads.indices_uniform(workloads.IDX_STREAM + k, M, N) for k in range(reps + W)]
+                ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+                nbytes = M * rb
+                kern = _stats(_kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev, out, W))
+                ok = ok and spot_check(table, N, D, oracle.F32, ids_np[-1], out, 512)
+                wall = _stats(_wall_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, [pinned(a) for a in ids_np], out, W))
+                _cpu_centric(bl, ctx, table.host_ptr, rb, ids_np[0], out.data_ptr(), threads)
+                py = sorted(_cpu_centric(bl, ctx, table.host_ptr, rb, a, out.data_ptr(), threads) for a in ids_np[1:6])[2]
+                ideal = nbytes / h2d_peak / 1e6
+                cells[f"({M // 1024}K, {rb}B)"] = {
+                    "MB": round(nbytes / 1e6, 2), "kernel_ms": kern["median_ms"], "call_to_sync_ms": wall["median_ms"],
+                    "cpu_centric_ms": round(py, 4), "ideal_ms": round(ideal, 4),
+                    "slowdown_vs_ideal": round(wall["median_ms"] / ideal, 3),
+                    "cpu_centric_slowdown_vs_ideal": round(py / ideal, 3),
+                    "speedup_vs_cpu_centric": round(py / wall["median_ms"], 3)}
+                tot_b += nbytes
+                tot_ms += kern["median_ms"]
+        bl.udb_cpu_centric_destroy(ctx)
+        return finish(tot_b / tot_ms / 1e6, tot_ms, "f32",
+                      {"workload": "size grid: 16 GiB host-pinned fp32 region viewed as rows of 256 B..16 KB, "
+                                   "8K..256K int64 IDs uniform; call-to-sync times include the ID list's H2D copy; "
+                                   "one step = one gather per cell", "cpu_centric_threads": threads},
+                      cells=cells, parity_spot_check=ok)
+    raise ValueError(wl)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +344,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--threads", type=int, default=0, help="host threads of the CPU-centric baseline (0 = all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host baselines (for profiling runs)")
+    ap.add_argument("--workload", default="sweep",
+                    choices=("sweep", "single", "graphsage", "large", "fp16", "align", "grid"),
+                    help="sweep (default, the headline microbenchmark) or one of the other configurations / "
+                         "the paper's alignment and size experiments")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the host-link gather has no multi-GPU path); "
@@ -91,6 +369,8 @@ def main() -> int:
     K, W = args.steps, args.warmup
     ncores = len(os.sched_getaffinity(0))
     threads = args.threads or min(ncores, 16)
+    if args.workload != "sweep":
+        return run_other(args, ud, bl, workloads, torch, np, threads, ncores)
 
     # ---- host-link peak: best of 10 pinned hipMemcpy H2D of 1 GiB, same process ----
     best, med = ctypes.c_double(), ctypes.c_double()

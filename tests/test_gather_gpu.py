@@ -70,7 +70,8 @@ def test_config1_single_gather(ud):
     t.free()
 
 
-WIDTHS = [1, 2, 3, 4, 5, 7, 16, 25, 64, 100, 127, 128, 129, 255, 256, 257, 300, 602, 603, 1031]
+WIDTHS = [1, 2, 3, 4, 5, 7, 16, 25, 64, 100, 127, 128, 129, 255, 256, 257, 300, 512, 513, 515, 518, 519, 602, 603,
+          1031, 4096, 4099]
 
 
 @pytest.mark.parametrize("D", WIDTHS)
