@@ -244,6 +244,67 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                                              "kernel_only": _stats(kern_h)},
                       parity_spot_check=ok)
 
+    if wl == "hybrid":
+        # hot-row cache in HBM on the two graph workloads: the most popular rows are read from HBM,
+        # the rest over the host link, in one kernel
+        cases = {}
+        stream = torch.cuda.current_stream().cuda_stream
+        ok = True
+        tot_b = tot_ms = 0.0
+        for name, p, N, seed, sseed, fracs in (("products_like", workloads.PRODUCTS_LIKE, 2_400_000, 3, 33, (0.01, 0.05, 0.2)),
+                                               ("papers_like", workloads.PAPERS_LIKE, 62_500_000, 4, 44, (0.01, 0.05, 0.256))):
+            D = p["D"]
+            table = ud.Table(N, D, ud.UD_F32)
+            workloads.fill_uniform_f32(table.host_ptr, seed, N * D)
+            nb = 10
+            if "mean_degree" in p:
+                offsets, nbr = workloads.zipf_graph_csr(N, p["mean_degree"], p["dmin"], p["alpha"], seed)
+                ids_np = [workloads.sample_csr(offsets, nbr, p["nseeds"], p["fanout"], sseed, b) for b in range(nb)]
+                del offsets, nbr
+            else:
+                ids_np = [workloads.sample_procedural(N, p["degree"], p["alpha"], seed, p["nseeds"], p["fanout"], sseed, b)
+                          for b in range(nb)]
+            ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+            out = torch.empty(max(a.size for a in ids_np) * D, dtype=torch.float32, device=dev)
+            rows = sum(a.size for a in ids_np)
+            useful = rows * D * 4
+            plain = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev[:W] + ids_dev, out, W)
+            r = {"plain_zero_copy_GBps": round(useful / sum(plain) / 1e6, 2), "caches": {}}
+            for frac in fracs:
+                n_hot = int(N * frac)
+                hot = workloads.hottest_nodes(N, n_hot, seed)
+                cache = ud.Cache(table, hot)
+                hits = sum(int(np.isin(a, hot[: n_hot]).sum()) if n_hot <= 5_000_000 else -1 for a in ids_np[:1])
+                ev = []
+                for k, ids in enumerate(ids_dev[:W] + ids_dev):
+                    if k >= W:
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                    ud.ud_gather_cached(cache.handle, ud.UD_F32, ids.data_ptr(), ud.UD_I64, ids.numel(), out.data_ptr(), stream)
+                    if k >= W:
+                        e1.record()
+                        ev.append((e0, e1))
+                torch.cuda.synchronize()
+                ud.ud_gather_status(stream)
+                ok = ok and spot_check(table, N, D, oracle.F32, ids_np[-1], out)
+                ms = [a.elapsed_time(b) for a, b in ev]
+                r["caches"][f"{frac:g}"] = {"rows_cached": n_hot, "hbm_GB": round(n_hot * D * 4 / 1e9 + N * 4 / 1e9, 2),
+                                            "effective_GBps": round(useful / sum(ms) / 1e6, 2),
+                                            "speedup_vs_plain": round(sum(plain) / sum(ms), 3),
+                                            "hit_fraction_batch0": round(hits / ids_np[0].size, 4) if hits >= 0 else None,
+                                            "kernel_only": _stats(ms)}
+                if frac == fracs[-1]:
+                    tot_b += useful
+                    tot_ms += sum(ms)
+                cache.free()
+            cases[name] = r
+            table.free()
+        return finish(tot_b / tot_ms / 1e6, tot_ms / 20, "f32",
+                      {"workload": "hybrid placement: hot-row cache in HBM (most popular rows by rank) over the host-pinned "
+                                   "table, on the two GraphSAGE-style workloads; value = useful bytes / time with the "
+                                   "largest cache; one step = one batch"},
+                      cases=cases, parity_spot_check=ok)
+
     if wl == "fp16":
         N, D, M = 10_000_000, 602, 2_000_000
         table = ud.Table(N, D, ud.UD_F16)
@@ -345,7 +406,7 @@ def main() -> int:
     ap.add_argument("--threads", type=int, default=0, help="host threads of the CPU-centric baseline (0 = all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host baselines (for profiling runs)")
     ap.add_argument("--workload", default="sweep",
-                    choices=("sweep", "single", "graphsage", "large", "fp16", "align", "grid"),
+                    choices=("sweep", "single", "graphsage", "large", "fp16", "align", "grid", "hybrid"),
                     help="sweep (default, the headline microbenchmark) or one of the other configurations / "
                          "the paper's alignment and size experiments")
     args = ap.parse_args()

@@ -122,6 +122,34 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
                     void *out, void *stream);
 
 /*
+ * Hot-row cache (hybrid placement).  The paper's placement discussion (Section
+ * 4.3) notes that data which is reused is better held in GPU memory than
+ * re-read over the host link; node IDs of power-law graphs are heavily skewed,
+ * so a small set of rows takes a large share of every minibatch.  A cache holds
+ * HBM copies of chosen rows of a host table plus a row -> slot map (one int32
+ * per table row, in HBM); ud_gather_cached reads a row from HBM when it is
+ * cached and over the host link otherwise, in one kernel.  Results are
+ * identical to ud_gather on the same table.
+ *
+ *   table     a host table (ud_alloc_table); must outlive the cache and must
+ *             not be written while the cache exists (cached copies would go stale)
+ *   hot_rows  host pointer to n_hot row IDs in [0, N); duplicates are tolerated
+ *   n_hot     1 .. min(N, 2^31 - 1)
+ * The call returns when the cache is filled.  HBM used: n_hot rows + 4 N bytes.
+ * Errors: UD_ERR_INVALID_ARG (NULL, device-resident table, bad n_hot or row ID),
+ * UD_ERR_OOM (HBM exhausted).
+ */
+typedef struct ud_cache ud_cache;
+ud_status ud_cache_create(const ud_table *table, const int64_t *hot_rows, int64_t n_hot, ud_cache **c);
+/* Releases the cache's HBM.  NULL is a no-op.  No gather that uses it may be in flight. */
+ud_status ud_cache_free(ud_cache *c);
+/* ud_gather on the cache's table (N, D and storage type are the table's): dtype must be
+ * UD_F32 for an fp32 table, UD_F16 or UD_F16_TO_F32 for an fp16 table.  Same
+ * asynchrony, ID-error behaviour and status reporting as ud_gather. */
+ud_status ud_gather_cached(const ud_cache *c, ud_dtype dtype, const void *idx, ud_itype itype, int64_t M,
+                           void *out, void *stream);
+
+/*
  * Kernel tuning for ud_gather_tuned; a zero field means "choose automatically".
  *   lanes_per_row    power of two in [1, 64]: lanes of a wavefront that share one row
  *   chunks_per_lane  1..4: 16-byte chunks of one row each lane keeps in flight

@@ -4,8 +4,26 @@
 memory (or in HBM), read directly by GPU wavefronts -- the hot path of
 PyTorch-Direct (arXiv 2101.07956, Sections 3 and 4.5).  The work is done by
 ``libud.so`` (C ABI in ``include/ud.h``); this package is its thin binding.
-Importing it fails loudly if the library has not been built.
+
+The compiled library is loaded on first use of any name of the binding
+(``ud_gather``, ``Table``, ...), so that ``paper_2101_07956_amd.build`` can be
+imported to compile it.  If the library has not been built that first use
+raises ImportError: there is no fallback path.
 """
-from .binding import *  # noqa: F401,F403
-from .binding import EXPORTS, LIB_PATH, UdError, UdIndexError, ud_tuning  # noqa: F401
-from .table import Table, gather  # noqa: F401
+from __future__ import annotations
+
+import importlib
+
+__all__ = ["binding", "table", "build"]
+
+
+def __getattr__(name: str):
+    if name.startswith("__"):
+        raise AttributeError(name)
+    binding = importlib.import_module(".binding", __name__)
+    if hasattr(binding, name):
+        return getattr(binding, name)
+    table = importlib.import_module(".table", __name__)
+    if hasattr(table, name):
+        return getattr(table, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

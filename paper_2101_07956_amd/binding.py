@@ -27,7 +27,7 @@ UD_TUNE_NT_LOAD, UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE = 1, 2, 4
 EXPORTS = (
     "ud_alloc_table", "ud_table_to_device", "ud_table_host_ptr", "ud_table_device_ptr",
     "ud_table_shape", "ud_free_table", "ud_gather", "ud_gather_tuned", "ud_gather_plan",
-    "ud_gather_status", "ud_status_str", "ud_last_hip_error",
+    "ud_gather_status", "ud_cache_create", "ud_cache_free", "ud_gather_cached", "ud_status_str", "ud_last_hip_error",
 )
 
 
@@ -75,6 +75,9 @@ _lib.ud_gather.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_gather_tuned.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp, ctypes.POINTER(ud_tuning)]
 _lib.ud_gather_plan.argtypes = [_vp, _i64, _int, ctypes.POINTER(ud_tuning)]
 _lib.ud_gather_status.argtypes = [_vp, ctypes.POINTER(_i64)]
+_lib.ud_cache_create.argtypes = [_vp, _vp, _i64, ctypes.POINTER(_vp)]
+_lib.ud_cache_free.argtypes = [_vp]
+_lib.ud_gather_cached.argtypes = [_vp, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_status_str.argtypes = [_int]
 _lib.ud_status_str.restype = ctypes.c_char_p
 _lib.ud_last_hip_error.argtypes = []
@@ -157,6 +160,21 @@ def ud_gather_status(stream: int | None = None) -> None:
     if st == UD_ERR_INDEX_OUT_OF_RANGE:
         raise UdIndexError(pos.value)
     _check(st, "ud_gather_status")
+
+
+def ud_cache_create(table: int, hot_rows_host_ptr: int, n_hot: int) -> int:
+    """Hot-row cache over a host table; ``hot_rows_host_ptr`` is the CPU address of ``n_hot`` int64 row IDs."""
+    c = _vp()
+    _check(_lib.ud_cache_create(table, hot_rows_host_ptr, n_hot, ctypes.byref(c)), "ud_cache_create")
+    return c.value
+
+
+def ud_cache_free(c: int | None) -> None:
+    _check(_lib.ud_cache_free(c), "ud_cache_free")
+
+
+def ud_gather_cached(cache: int, dtype: int, idx: int, itype: int, M: int, out: int, stream: int | None = None) -> None:
+    _check(_lib.ud_gather_cached(cache, dtype, idx, itype, M, out, stream), "ud_gather_cached")
 
 
 def raw_status(fn_name: str, *args) -> int:

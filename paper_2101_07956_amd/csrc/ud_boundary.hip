@@ -21,6 +21,15 @@ struct ud_table {
     bool device_resident;
 };
 
+struct ud_cache {
+    const void *table; // GPU address of the host table's row 0
+    int64_t N, D;
+    ud_dtype elem;
+    void *rows;        // HBM copy of the hot rows, slot-major
+    int32_t *slot;     // HBM, N entries: slot of each table row in `rows`, or -1
+    int64_t n_hot;
+};
+
 namespace {
 
 thread_local char g_hip_msg[256] = "";
@@ -262,9 +271,10 @@ ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning
     return UD_OK;
 }
 
-ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtype,
-                          const void *idx, ud_itype itype, int64_t M,
-                          void *out, void *stream, const ud_tuning *tuning)
+static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                             const void *idx, ud_itype itype, int64_t M,
+                             void *out, void *stream, const ud_tuning *tuning,
+                             const int32_t *slot, const char *cache)
 {
     if (N < 1 || D < 1 || M < 0)
         return UD_ERR_INVALID_ARG;
@@ -323,6 +333,8 @@ ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtyp
     a.itype = itype;
     a.M = M;
     a.out = out;
+    a.slot = slot;
+    a.cache = cache;
     const ud_status es = error_word(&a.err);
     if (es != UD_OK)
         return es;
@@ -344,11 +356,94 @@ ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtyp
     return UD_OK;
 }
 
+ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                          const void *idx, ud_itype itype, int64_t M,
+                          void *out, void *stream, const ud_tuning *tuning)
+{
+    return gather_impl(table, N, D, dtype, idx, itype, M, out, stream, tuning, nullptr, nullptr);
+}
+
 ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
                     const void *idx, ud_itype itype, int64_t M,
                     void *out, void *stream)
 {
-    return ud_gather_tuned(table, N, D, dtype, idx, itype, M, out, stream, nullptr);
+    return gather_impl(table, N, D, dtype, idx, itype, M, out, stream, nullptr, nullptr, nullptr);
+}
+
+ud_status ud_cache_create(const ud_table *table, const int64_t *hot_rows, int64_t n_hot, ud_cache **c)
+{
+    if (!table || !c || table->device_resident || n_hot < 1 || n_hot > table->N || n_hot > INT32_MAX || !hot_rows)
+        return UD_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < n_hot; ++k)
+        if (hot_rows[k] < 0 || hot_rows[k] >= table->N)
+            return UD_ERR_INVALID_ARG;
+    const int64_t row_bytes = table->D * elem_bytes(table->elem);
+    ud_cache *h = new (std::nothrow) ud_cache{};
+    if (!h)
+        return UD_ERR_OOM;
+    h->table = table->dev;
+    h->N = table->N;
+    h->D = table->D;
+    h->elem = table->elem;
+    h->n_hot = n_hot;
+    int64_t *ids_dev = nullptr;
+    ud_status st = UD_OK;
+    hipError_t e = hipMalloc(&h->rows, static_cast<size_t>(n_hot) * static_cast<size_t>(row_bytes));
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void **>(&h->slot), static_cast<size_t>(table->N) * sizeof(int32_t));
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void **>(&ids_dev), static_cast<size_t>(n_hot) * sizeof(int64_t));
+    if (e == hipSuccess)
+        e = hipMemcpy(ids_dev, hot_rows, static_cast<size_t>(n_hot) * sizeof(int64_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemset(h->slot, 0xff, static_cast<size_t>(table->N) * sizeof(int32_t)); // every row: slot -1
+    if (e != hipSuccess)
+        st = hip_fail(e, "ud_cache_create");
+    // the cache is filled by the library's own zero-copy gather, then the map is scattered
+    if (st == UD_OK)
+        st = gather_impl(table->dev, table->N, table->D, table->elem, ids_dev, UD_I64, n_hot, h->rows, nullptr, nullptr,
+                         nullptr, nullptr);
+    if (st == UD_OK) {
+        e = ud::launch_fill_slots(ids_dev, n_hot, h->slot, nullptr);
+        if (e == hipSuccess)
+            e = hipStreamSynchronize(nullptr);
+        if (e != hipSuccess)
+            st = hip_fail(e, "ud_cache_create(slot map)");
+    }
+    if (ids_dev)
+        (void)hipFree(ids_dev);
+    if (st != UD_OK) {
+        (void)ud_cache_free(h);
+        return st;
+    }
+    *c = h;
+    return UD_OK;
+}
+
+ud_status ud_cache_free(ud_cache *c)
+{
+    if (!c)
+        return UD_OK;
+    hipError_t e1 = c->rows ? hipFree(c->rows) : hipSuccess;
+    hipError_t e2 = c->slot ? hipFree(c->slot) : hipSuccess;
+    delete c;
+    if (e1 != hipSuccess)
+        return hip_fail(e1, "hipFree(cache rows)");
+    if (e2 != hipSuccess)
+        return hip_fail(e2, "hipFree(cache map)");
+    return UD_OK;
+}
+
+ud_status ud_gather_cached(const ud_cache *c, ud_dtype dtype, const void *idx, ud_itype itype, int64_t M,
+                           void *out, void *stream)
+{
+    if (!c)
+        return UD_ERR_INVALID_ARG;
+    // the table's storage type must match the gather's input type
+    if ((dtype == UD_F32) != (c->elem == UD_F32))
+        return UD_ERR_INVALID_ARG;
+    return gather_impl(c->table, c->N, c->D, dtype, idx, itype, M, out, stream, nullptr, c->slot,
+                       static_cast<const char *>(c->rows));
 }
 
 ud_status ud_gather_status(void *stream, int64_t *bad_pos)

@@ -21,14 +21,33 @@ __global__ __launch_bounds__(kBlockThreads) void gather_elementwise(GatherArgs a
                 atomicMin(a.err, static_cast<unsigned long long>(i));
             continue;
         }
-        const int64_t src = r * a.D + j;
+        constexpr int IN_ESZ = (DT == UD_F32) ? 4 : 2;
+        const char *row = row_source(a, r, a.D * IN_ESZ);
         if constexpr (DT == UD_F32)
-            static_cast<uint32_t *>(a.out)[g] = reinterpret_cast<const uint32_t *>(a.table)[src];
+            static_cast<uint32_t *>(a.out)[g] = reinterpret_cast<const uint32_t *>(row)[j];
         else if constexpr (DT == UD_F16)
-            static_cast<uint16_t *>(a.out)[g] = reinterpret_cast<const uint16_t *>(a.table)[src];
+            static_cast<uint16_t *>(a.out)[g] = reinterpret_cast<const uint16_t *>(row)[j];
         else
-            static_cast<uint32_t *>(a.out)[g] = widen_half(reinterpret_cast<const uint16_t *>(a.table)[src]);
+            static_cast<uint32_t *>(a.out)[g] = widen_half(reinterpret_cast<const uint16_t *>(row)[j]);
     }
+}
+
+__global__ __launch_bounds__(kBlockThreads) void fill_slots(const int64_t *rows, int64_t n, int32_t *slot)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlockThreads;
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kBlockThreads + threadIdx.x; k < n; k += stride)
+        slot[rows[k]] = static_cast<int32_t>(k);
+}
+
+hipError_t launch_fill_slots(const int64_t *rows, int64_t n, int32_t *slot, hipStream_t s)
+{
+    int64_t blocks = (n + kBlockThreads - 1) / kBlockThreads;
+    if (blocks > 65536)
+        blocks = 65536;
+    if (blocks < 1)
+        return hipSuccess;
+    hipLaunchKernelGGL(fill_slots, dim3(static_cast<unsigned>(blocks)), dim3(kBlockThreads), 0, s, rows, n, slot);
+    return hipGetLastError();
 }
 
 hipError_t launch_elementwise(const GatherArgs &a, int dtype, const Plan &p, hipStream_t s)

@@ -80,6 +80,18 @@ __device__ __forceinline__ int64_t load_id(const void *idx, int itype, int64_t i
                            : static_cast<int64_t>(static_cast<const int32_t *>(idx)[i]);
 }
 
+// Where row r is read from: its slot in the HBM hot-row cache if it has one,
+// else the table itself.
+__device__ __forceinline__ const char *row_source(const GatherArgs &a, int64_t r, int64_t row_bytes)
+{
+    if (a.slot) {
+        const int32_t s = a.slot[r];
+        if (s >= 0)
+            return a.cache + static_cast<int64_t>(s) * row_bytes;
+    }
+    return a.table + r * row_bytes;
+}
+
 // Exact binary16 -> binary32.  The hardware converter widens every finite
 // value and infinity exactly (fp16 subnormals are never flushed: the f16
 // denormal mode is "preserve").  NaNs are rebuilt from the bits so that the
@@ -165,7 +177,7 @@ __global__ __launch_bounds__(kBlockThreads) void gather_chunked(GatherArgs a, in
                     if (l == 0)
                         atomicMin(a.err, static_cast<unsigned long long>(i[u]));
                 } else {
-                    const char *src = a.table + r * row_bytes;
+                    const char *src = row_source(a, r, row_bytes);
                     head[u] = static_cast<int>(reinterpret_cast<uintptr_t>(src) & 15u);
                     base[u] = src - head[u];
                     nch[u] = (head[u] + row_bytes + 15) >> 4;

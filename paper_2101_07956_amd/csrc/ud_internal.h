@@ -19,6 +19,10 @@ struct GatherArgs {
     int64_t M;
     void *out;               // device pointer, M x D output elements
     unsigned long long *err; // device error word (atomic min of bad positions)
+    // hot-row cache (both null when unused): slot[r] >= 0 means row r is read
+    // from cache + slot[r] * row_bytes (HBM) instead of table + r * row_bytes
+    const int32_t *slot;
+    const char *cache;
 };
 
 // Resolved kernel parameters (every field concrete, see ud_tuning).
@@ -39,6 +43,9 @@ constexpr int kBlockThreads = 64 * kWavesPerBlock;
 hipError_t launch_chunked_f32(const GatherArgs &a, const Plan &p, hipStream_t s);
 hipError_t launch_chunked_f16(const GatherArgs &a, const Plan &p, hipStream_t s);
 hipError_t launch_chunked_f16_to_f32(const GatherArgs &a, const Plan &p, hipStream_t s);
+
+// slot[rows[k]] = k for k < n (building a hot-row cache's map).
+hipError_t launch_fill_slots(const int64_t *rows, int64_t n, int32_t *slot, hipStream_t s);
 
 // Enqueue the one-lane-per-element gather.
 hipError_t launch_elementwise(const GatherArgs &a, int dtype, const Plan &p, hipStream_t s);

@@ -53,6 +53,27 @@ class Table:
             pass
 
 
+class Cache:
+    """HBM copies of chosen rows of a host table plus the row -> slot map (hybrid placement)."""
+
+    def __init__(self, table: Table, hot_rows: np.ndarray):
+        hot_rows = np.ascontiguousarray(hot_rows, dtype=np.int64)
+        self.table = table                      # keeps the host table alive
+        self.n_hot = int(hot_rows.size)
+        self.handle = B.ud_cache_create(table.handle, hot_rows.ctypes.data, hot_rows.size)
+
+    def free(self) -> None:
+        if self.handle:
+            B.ud_cache_free(self.handle)
+            self.handle = None
+
+    def __del__(self):  # pragma: no cover - best effort
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
 def gather(table: Table, idx, out=None, widen: bool = False, tuning: B.ud_tuning | None = None, check: bool = False):
     """``out[i, :] = table[idx[i], :]`` for a torch int64/int32 CUDA tensor ``idx``.
 

@@ -90,6 +90,9 @@ def test_table_calls_reject_bad_arguments(ud):
     assert rs("ud_table_device_ptr", None, ctypes.byref(t)) == inv
     assert rs("ud_table_shape", None, None, None, None) == inv
     assert rs("ud_free_table", None) == ud.UD_OK                          # NULL is a no-op
+    assert rs("ud_cache_create", None, None, 1, ctypes.byref(t)) == inv
+    assert rs("ud_gather_cached", None, 0, 0x1000, 0, 1, 0x2000, None) == inv
+    assert rs("ud_cache_free", None) == ud.UD_OK
 
 
 def test_plan_follows_row_width(ud):

@@ -295,3 +295,77 @@ def test_plan_depends_on_where_the_table_lives(ud):
     assert dev_plan.lanes_per_row == 32 and dev_plan.rows_in_flight == 2 and dev_plan.flags == ud.UD_TUNE_NT_STORE
     d.free()
     t.free()
+
+
+# ---- hot-row cache (hybrid placement): same results as the plain gather ----
+
+def run_cached(ud, cache, dtype, idx_np, D):
+    M = idx_np.size
+    obytes = 2 if dtype == ud.UD_F16 else 4
+    buf = torch.full(((M * D + 64) * obytes,), CANARY, dtype=torch.uint8, device="cuda")
+    idx = torch.from_numpy(idx_np).cuda()
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_gather_cached(cache.handle, dtype, idx.data_ptr(), ud.UD_I64 if idx_np.dtype == np.int64 else ud.UD_I32,
+                        M, buf.data_ptr(), s)
+    ud.ud_gather_status(s)
+    host = buf.cpu().numpy()
+    assert (host[M * D * obytes:] == CANARY).all()
+    return host[: M * D * obytes].view(np.uint16 if obytes == 2 else np.uint32).reshape(M, D)
+
+
+@pytest.mark.parametrize("D", [16, 100, 128, 602])
+def test_cached_gather_equals_oracle_fp32(ud, D):
+    N, M = 30_011, 20_003
+    t = make_table(ud, N, D, ud.UD_F32, 400 + D)
+    rng = np.random.default_rng(D)
+    for n_hot in (1, 977, N):                                   # one row, a few, every row
+        hot = rng.permutation(N)[:n_hot].astype(np.int64)
+        c = ud.Cache(t, hot)
+        for idt in (np.int64, np.int32):
+            idx = workloads.indices_uniform(40 + n_hot, M, N, idt)
+            idx[: min(n_hot, 50)] = hot[: min(n_hot, 50)]       # make sure cached rows are hit
+            idx[-2:] = [0, N - 1]
+            got = run_cached(ud, c, ud.UD_F32, idx, D)
+            assert np.array_equal(got, oracle_bits(t.numpy(), idx, oracle.F32)), (D, n_hot, idt)
+        c.free()
+    t.free()
+
+
+def test_cached_gather_reads_the_cached_copy(ud):
+    # after the cache is built the host rows are overwritten: cached rows must come from HBM
+    # (old values), uncached rows over the link (new values)
+    N, D, M = 5000, 64, 4000
+    t = make_table(ud, N, D, ud.UD_F32, 41)
+    old = t.numpy().copy()
+    hot = np.arange(0, N, 3, dtype=np.int64)
+    c = ud.Cache(t, hot)
+    t.numpy()[:] = old + 1.0
+    idx = workloads.indices_uniform(42, M, N)
+    got = run_cached(ud, c, ud.UD_F32, idx, D).view(np.float32)
+    is_hot = (idx % 3) == 0
+    assert is_hot.any() and (~is_hot).any()
+    assert np.array_equal(got[is_hot], old[idx[is_hot]])
+    assert np.array_equal(got[~is_hot], (old + 1.0)[idx[~is_hot]])
+    c.free()
+    t.free()
+
+
+def test_cached_gather_fp16_and_errors(ud):
+    N, D, M = 9001, 301, 7000
+    t = make_table(ud, N, D, ud.UD_F16, 43)
+    hot = workloads.indices_uniform(44, 2000, N)                # duplicates tolerated
+    c = ud.Cache(t, hot)
+    idx = workloads.indices_uniform(45, M, N, np.int32)
+    for dtype in (ud.UD_F16, ud.UD_F16_TO_F32):
+        assert np.array_equal(run_cached(ud, c, dtype, idx, D), oracle_bits(t.numpy(), idx, dtype))
+    bad = idx.copy()
+    bad[1234] = N
+    with pytest.raises(ud.UdIndexError) as e:
+        run_cached(ud, c, ud.UD_F16, bad, D)
+    assert e.value.pos == 1234
+    with pytest.raises(ud.UdError):                             # fp32 gather on an fp16 table
+        ud.ud_gather_cached(c.handle, ud.UD_F32, 0x1000, ud.UD_I64, 1, 0x2000, None)
+    with pytest.raises(ud.UdError):                             # hot row out of range
+        ud.Cache(t, np.array([0, N], dtype=np.int64))
+    c.free()
+    t.free()

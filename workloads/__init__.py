@@ -59,6 +59,8 @@ def lib():
         _dbl = ctypes.c_double
         L.wl_node_of_rank.restype = _i64
         L.wl_node_of_rank.argtypes = [_u64, _u64, _u64]
+        L.wl_nodes_of_ranks.restype = None
+        L.wl_nodes_of_ranks.argtypes = [_vp, _u64, _u64, _u64, _u64]
         L.wl_zipf_rank.restype = _u64
         L.wl_zipf_rank.argtypes = [_u64, _u64, _u64, _dbl]
         L.wl_graph_degrees.restype = _i64
@@ -140,6 +142,13 @@ def zipf_graph_csr(N: int, mean_degree: float, dmin: int, alpha: float, seed: in
     ids = np.empty(total, dtype=np.int64)
     lib().wl_graph_fill_ids(offsets.ctypes.data, ids.ctypes.data, N, float(alpha), seed)
     return offsets, ids
+
+
+def hottest_nodes(N: int, n: int, graph_seed: int) -> np.ndarray:
+    """The ``n`` most popular nodes of a graph built with ``graph_seed`` (popularity ranks 1..n)."""
+    out = np.empty(n, dtype=np.int64)
+    lib().wl_nodes_of_ranks(out.ctypes.data, 1, n, N, graph_seed)
+    return out
 
 
 def slot_bound(nseeds: int, fanout) -> int:

@@ -65,6 +65,15 @@ int64_t wl_node_of_rank(uint64_t rank, uint64_t N, uint64_t seed)
     return node_of_rank0(rank - 1, N, A, B);
 }
 
+/* out[k] = node whose popularity rank is first_rank + k (ranks start at 1) */
+void wl_nodes_of_ranks(int64_t *out, uint64_t first_rank, uint64_t n, uint64_t N, uint64_t seed)
+{
+    uint64_t A, B;
+    perm_params(N, seed, &A, &B);
+    for (uint64_t k = 0; k < n; ++k)
+        out[k] = node_of_rank0(first_rank - 1 + k, N, A, B);
+}
+
 /* rank in [1, N] with P(rank = k) ~ k^-alpha, from one 64-bit hash */
 static inline uint64_t rank_from_hash(uint64_t h, uint64_t N, double alpha)
 {
