@@ -56,6 +56,12 @@ def _load():
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
             ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
         ]
+        lib.oracle_scatter.restype = ctypes.c_int
+        lib.oracle_scatter.argtypes = [
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+            ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
+        ]
         lib.oracle_count_requests.restype = ctypes.c_int64
         lib.oracle_count_requests.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
@@ -104,6 +110,29 @@ def gather(table: np.ndarray, idx: np.ndarray, dtype: int | None = None) -> np.n
     if dtype == F16_TO_F32:
         return out.view(np.float32)
     return out.view(table.dtype)
+
+
+def scatter_raw(table_ptr: int, N: int, D: int, dtype: int, idx: np.ndarray, src: np.ndarray) -> None:
+    """Oracle scatter into a table at a raw host address: ``table[idx[i], :] = src[i, :]``, in order of i."""
+    itype = {np.dtype(np.int64): I64, np.dtype(np.int32): I32}[idx.dtype]
+    assert idx.flags.c_contiguous and src.flags.c_contiguous
+    bad = ctypes.c_int64(-1)
+    rc = _load().oracle_scatter(table_ptr, N, D, dtype, idx.ctypes.data, itype, idx.size,
+                                src.ctypes.data, ctypes.byref(bad))
+    if rc == ERR_INDEX:
+        raise OracleIndexError(bad.value)
+    if rc != OK:
+        raise ValueError(f"oracle_scatter: invalid argument (status {rc})")
+
+
+def scatter(table: np.ndarray, idx: np.ndarray, src: np.ndarray) -> None:
+    """In place: ``table[idx[i], :] = src[i, :]`` for i = 0, 1, ... (the last duplicate wins)."""
+    assert table.ndim == 2 and table.flags.c_contiguous and table.flags.writeable
+    assert src.dtype.itemsize == table.dtype.itemsize and src.shape == (idx.size, table.shape[1])
+    idx = np.ascontiguousarray(idx)
+    src = np.ascontiguousarray(src)
+    dtype = F32 if table.dtype.itemsize == 4 else F16
+    scatter_raw(table.ctypes.data, table.shape[0], table.shape[1], dtype, idx, src)
 
 
 def f16_bits_to_f32_bits(h: np.ndarray) -> np.ndarray:

@@ -210,3 +210,50 @@ int64_t oracle_circular_shift(int64_t i, int64_t r, int64_t D, int64_t elems_per
         s += elems_per_line;
     return s;
 }
+
+/*
+ * Write direction: table[idx[i]*D + j] = src[i*D + j]  for 0 <= i < M, 0 <= j < D,
+ * applied in the order i = 0, 1, ..., so with duplicate IDs the last occurrence
+ * wins.  The paper states (Section 3) that GPU threads can issue both read and
+ * write requests to host memory; this is the gather's mirror image, needed
+ * e.g. to update rows of a host-resident table.  Bit patterns are copied; dtype
+ * is ORACLE_F32 (4-byte elements) or ORACLE_F16 (2-byte elements).
+ * All IDs are checked before anything is written; on a bad ID *bad_pos is its
+ * first position, ORACLE_ERR_INDEX is returned and the table is untouched.
+ */
+int oracle_scatter(void *table, int64_t N, int64_t D, int dtype,
+                   const void *idx, int itype, int64_t M,
+                   const void *src, int64_t *bad_pos)
+{
+    if (bad_pos)
+        *bad_pos = -1;
+    if (N < 1 || D < 1 || M < 0)
+        return ORACLE_ERR_INVALID_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_F16)
+        return ORACLE_ERR_INVALID_ARG;
+    if (itype != ORACLE_I64 && itype != ORACLE_I32)
+        return ORACLE_ERR_INVALID_ARG;
+    if (M == 0)
+        return ORACLE_OK;
+    if (!table || !idx || !src)
+        return ORACLE_ERR_INVALID_ARG;
+
+    for (int64_t i = 0; i < M; ++i) {
+        const int64_t r = read_index(idx, itype, i);
+        if (r < 0 || r >= N) {
+            if (bad_pos)
+                *bad_pos = i;
+            return ORACLE_ERR_INDEX;
+        }
+    }
+    for (int64_t i = 0; i < M; ++i) {
+        const int64_t r = read_index(idx, itype, i);
+        for (int64_t j = 0; j < D; ++j) {
+            if (dtype == ORACLE_F32)
+                ((uint32_t *)table)[r * D + j] = ((const uint32_t *)src)[i * D + j];
+            else
+                ((uint16_t *)table)[r * D + j] = ((const uint16_t *)src)[i * D + j];
+        }
+    }
+    return ORACLE_OK;
+}
