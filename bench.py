@@ -43,6 +43,7 @@ def _load_baseline_lib(ud):
     dp = ctypes.POINTER(ctypes.c_double)
     bl.udb_h2d_peak.argtypes = [ctypes.c_size_t, ctypes.c_int, dp, dp]
     bl.udb_d2d_peak.argtypes = [ctypes.c_size_t, ctypes.c_int, dp, dp]
+    bl.udb_d2h_peak.argtypes = [ctypes.c_size_t, ctypes.c_int, dp, dp]
     bl.udb_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     bl.udb_cpu_centric_create.argtypes = [ctypes.c_size_t, ctypes.POINTER(ctypes.c_void_p)]
     bl.udb_cpu_centric_destroy.argtypes = [ctypes.c_void_p]
@@ -305,6 +306,156 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                                    "largest cache; one step = one batch"},
                       cases=cases, parity_spot_check=ok)
 
+    if wl == "scatter":
+        # write direction: rows scattered from HBM into the host-pinned table (distinct IDs)
+        best, med = ctypes.c_double(), ctypes.c_double()
+        bl.udb_d2h_peak(1 << 30, 10, ctypes.byref(best), ctypes.byref(med))
+        d2h_peak = best.value
+        N, M = N_ROWS, M_ROWS
+        dmax = max(WIDTHS)
+        table = ud.Table(N, dmax, ud.UD_F32)
+        workloads.fill_uniform_f32(table.host_ptr, 8, N * dmax)
+        src = torch.empty(M * dmax, dtype=torch.float32, device=dev).uniform_(-1, 1)
+        reps = min(K, 10)
+        perms = [np.random.default_rng(k).permutation(N)[:M].astype(np.int64) for k in range(reps + W)]
+        ids_dev = [torch.from_numpy(a).to(dev) for a in perms]
+        stream = torch.cuda.current_stream().cuda_stream
+        devt = table.to_device()
+        rows, ok = {}, True
+        tot_b = tot_ms = 0.0
+        for D in WIDTHS:
+            per = {}
+            for where, tptr in (("host", table.device_ptr), ("hbm", devt.device_ptr)):
+                ev = []
+                for k, ids in enumerate(ids_dev):
+                    if k >= W:
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                    ud.ud_scatter(tptr, N, D, ud.UD_F32, ids.data_ptr(), ud.UD_I64, M, src.data_ptr(), stream)
+                    if k >= W:
+                        e1.record()
+                        ev.append((e0, e1))
+                torch.cuda.synchronize()
+                ud.ud_gather_status(stream)
+                per[where] = _stats([a.elapsed_time(b) for a, b in ev])
+            # spot check on the host table: sampled rows of the last scatter equal their source rows
+            samp = np.sort(np.random.default_rng(1).choice(M, 2048, replace=False))
+            last = perms[-1]
+            want = src[: M * D].view(M, D)[torch.from_numpy(samp).to(dev)].cpu().numpy()
+            got = np.empty((samp.size, D), dtype=np.uint32)
+            oracle.gather_raw(table.host_ptr, N, D, oracle.F32, np.ascontiguousarray(last[samp]), got)
+            ok = ok and bool(np.array_equal(got, want.view(np.uint32)))
+            nbytes = M * D * 4
+            rows[str(D)] = {"row_bytes": D * 4, "host_ms": per["host"]["median_ms"],
+                            "host_GBps": round(nbytes / per["host"]["median_ms"] / 1e6, 2),
+                            "frac_of_d2h_peak": round(nbytes / per["host"]["median_ms"] / 1e6 / d2h_peak, 4),
+                            "hbm_GBps_read_plus_write": round(2 * nbytes / per["hbm"]["median_ms"] / 1e6, 1)}
+            tot_b += nbytes
+            tot_ms += per["host"]["median_ms"]
+        devt.free()
+        res["d2h_peak_GBps"] = round(d2h_peak, 2)
+        return finish(tot_b / tot_ms / 1e6, tot_ms, "f32",
+                      {"workload": "write direction: 1,000,000 distinct rows scattered from HBM into a host-pinned fp32 table "
+                                   "4,000,000 x D, D in {16,64,100,128,256,602}; one step = one scatter per width"},
+                      per_width=rows, frac_of_d2h_peak=round(tot_b / tot_ms / 1e6 / d2h_peak, 4), parity_spot_check=ok)
+
+    if wl == "overlap":
+        # gather for batch b+1 on a second stream while a stand-in consumer (dense layers on the gathered
+        # features) works on batch b: how much of the gather time disappears behind compute
+        p = workloads.PAPERS_LIKE
+        N, D = 16_000_000, p["D"]
+        table = ud.Table(N, D, ud.UD_F32)
+        workloads.fill_uniform_f32(table.host_ptr, 4, N * D)
+        nb = 12
+        ids_np = [workloads.sample_procedural(N, p["degree"], p["alpha"], 4, p["nseeds"], p["fanout"], 44, b) for b in range(nb)]
+        M = min(a.size for a in ids_np)
+        ids_dev = [torch.from_numpy(np.ascontiguousarray(a[:M])).to(dev) for a in ids_np]
+        bufs = [torch.empty((M, D), dtype=torch.float32, device=dev) for _ in range(2)]
+        hidden = 1024
+        w1 = torch.randn(D, hidden, device=dev) * 0.05
+        w2 = torch.randn(hidden, hidden, device=dev) * 0.05
+        layers = 1
+
+        def consume(x):
+            h = torch.relu(x @ w1)
+            for _ in range(layers):
+                h = torch.relu(h @ w2)
+            return h.sum()
+
+        sg, sc = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def gather_on(stream, b, buf, tun):
+            ud.ud_gather_tuned(table.device_ptr, N, D, ud.UD_F32, ids_dev[b].data_ptr(), ud.UD_I64, M, buf.data_ptr(),
+                               stream.cuda_stream, tun)
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3
+
+        def only_gather(tun):
+            def f():
+                for b in range(nb):
+                    gather_on(sg, b, bufs[b & 1], tun)
+            return f
+
+        def only_compute():
+            with torch.cuda.stream(sc):
+                for b in range(nb):
+                    consume(bufs[b & 1])
+
+        # size the consumer so that it takes a little longer than one gather
+        t_g = timed(only_gather(None)) / nb
+        while True:
+            t_c = timed(only_compute) / nb
+            if t_c >= 1.2 * t_g or layers >= 64:
+                break
+            layers = max(layers + 1, int(layers * 1.2 * t_g / max(t_c, 1e-3)))
+
+        def serial(tun):
+            def f():
+                with torch.cuda.stream(sc):
+                    for b in range(nb):
+                        gather_on(sc, b, bufs[b & 1], tun)
+                        consume(bufs[b & 1])
+            return f
+
+        def overlapped(tun):
+            def f():
+                g_done = [torch.cuda.Event() for _ in range(nb)]
+                c_done = [torch.cuda.Event() for _ in range(nb)]
+                for b in range(nb):
+                    if b >= 2:
+                        sg.wait_event(c_done[b - 2])            # buffer b&1 is free again
+                    gather_on(sg, b, bufs[b & 1], tun)
+                    g_done[b].record(sg)
+                    sc.wait_event(g_done[b])
+                    with torch.cuda.stream(sc):
+                        consume(bufs[b & 1])
+                    c_done[b].record(sc)
+            return f
+
+        variants = {}
+        for name, tun in (("auto", None), ("64_workgroups", ud.ud_tuning(0, 0, 0, 64, 0)),
+                          ("16_workgroups", ud.ud_tuning(0, 0, 0, 16, 0))):
+            tg = timed(only_gather(tun)) / nb
+            ts = timed(serial(tun)) / nb
+            to = timed(overlapped(tun)) / nb
+            variants[name] = {"gather_only_ms": round(tg, 3), "serial_ms": round(ts, 3), "overlapped_ms": round(to, 3),
+                              "exposed_gather_ms": round(max(to - t_c, 0.0), 3),
+                              "hidden_fraction_of_gather": round(1.0 - max(to - t_c, 0.0) / tg, 3)}
+        ud.ud_gather_status(sg.cuda_stream)
+        ok = spot_check(table, N, D, oracle.F32, np.ascontiguousarray(ids_np[nb - 1][:M]), bufs[(nb - 1) & 1].view(-1))
+        best = min(variants.values(), key=lambda v: v["overlapped_ms"])
+        return finish(M * D * 4 / best["overlapped_ms"] / 1e6, best["overlapped_ms"], "f32",
+                      {"workload": f"overlap: zero-copy gather of batch b+1 ({M} rows x 1024 B from a 16,000,000-row host table) "
+                                   f"on one stream while {layers + 1} dense fp32 layers (hidden {hidden}) consume batch b on another; "
+                                   "value = gathered bytes / per-batch time of the overlapped pipeline"},
+                      compute_only_ms=round(t_c, 3), variants=variants, parity_spot_check=ok)
+
     if wl == "fp16":
         N, D, M = 10_000_000, 602, 2_000_000
         table = ud.Table(N, D, ud.UD_F16)
@@ -406,7 +557,7 @@ def main() -> int:
     ap.add_argument("--threads", type=int, default=0, help="host threads of the CPU-centric baseline (0 = all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host baselines (for profiling runs)")
     ap.add_argument("--workload", default="sweep",
-                    choices=("sweep", "single", "graphsage", "large", "fp16", "align", "grid", "hybrid"),
+                    choices=("sweep", "single", "graphsage", "large", "fp16", "align", "grid", "hybrid", "scatter", "overlap"),
                     help="sweep (default, the headline microbenchmark) or one of the other configurations / "
                          "the paper's alignment and size experiments")
     args = ap.parse_args()

@@ -181,6 +181,32 @@ ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtyp
                           const void *idx, ud_itype itype, int64_t M,
                           void *out, void *stream, const ud_tuning *tuning);
 
+/*
+ * Write direction: table[idx[i], j] = src[i, j]  for 0 <= i < M, 0 <= j < D.
+ * The paper notes (Section 3) that a GPU which dereferences host memory issues
+ * write requests on the host link as well as reads; this is the gather's
+ * mirror image, e.g. for updating rows of a host-resident table from the GPU.
+ *
+ *   table  device pointer to N x D elements (host-mapped or HBM), written
+ *   dtype  UD_F32 or UD_F16 (bit copy; UD_F16_TO_F32 is an invalid argument)
+ *   idx    device pointer (HBM) to M row IDs.  IDs should be distinct: if an ID
+ *          occurs more than once, each element of that row receives the value
+ *          from one of its source rows, which one is unspecified
+ *   src    device pointer (HBM) to M x D dense source elements; must not
+ *          overlap table
+ * Asynchronous on stream like ud_gather; the CPU may read the rows of a host
+ * table after the stream has been synchronised (ud_gather_status does).
+ * Rows whose ID is out of range are skipped and reported through
+ * ud_gather_status exactly as for ud_gather.  Errors as ud_gather.
+ */
+ud_status ud_scatter(void *table, int64_t N, int64_t D, ud_dtype dtype,
+                     const void *idx, ud_itype itype, int64_t M,
+                     const void *src, void *stream);
+/* ud_scatter with explicit kernel parameters (tuning->flags must be 0). */
+ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
+                           const void *idx, ud_itype itype, int64_t M,
+                           const void *src, void *stream, const ud_tuning *tuning);
+
 /* The parameters ud_gather would pick for this shape and table alignment (no launch). */
 ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning *plan);
 

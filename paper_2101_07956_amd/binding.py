@@ -27,7 +27,8 @@ UD_TUNE_NT_LOAD, UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE = 1, 2, 4
 EXPORTS = (
     "ud_alloc_table", "ud_table_to_device", "ud_table_host_ptr", "ud_table_device_ptr",
     "ud_table_shape", "ud_free_table", "ud_gather", "ud_gather_tuned", "ud_gather_plan",
-    "ud_gather_status", "ud_cache_create", "ud_cache_free", "ud_gather_cached", "ud_status_str", "ud_last_hip_error",
+    "ud_gather_status", "ud_cache_create", "ud_cache_free", "ud_gather_cached",
+    "ud_scatter", "ud_scatter_tuned", "ud_status_str", "ud_last_hip_error",
 )
 
 
@@ -75,6 +76,8 @@ _lib.ud_gather.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_gather_tuned.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp, ctypes.POINTER(ud_tuning)]
 _lib.ud_gather_plan.argtypes = [_vp, _i64, _int, ctypes.POINTER(ud_tuning)]
 _lib.ud_gather_status.argtypes = [_vp, ctypes.POINTER(_i64)]
+_lib.ud_scatter.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
+_lib.ud_scatter_tuned.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp, ctypes.POINTER(ud_tuning)]
 _lib.ud_cache_create.argtypes = [_vp, _vp, _i64, ctypes.POINTER(_vp)]
 _lib.ud_cache_free.argtypes = [_vp]
 _lib.ud_gather_cached.argtypes = [_vp, _int, _vp, _int, _i64, _vp, _vp]
@@ -160,6 +163,15 @@ def ud_gather_status(stream: int | None = None) -> None:
     if st == UD_ERR_INDEX_OUT_OF_RANGE:
         raise UdIndexError(pos.value)
     _check(st, "ud_gather_status")
+
+
+def ud_scatter(table: int, N: int, D: int, dtype: int, idx: int, itype: int, M: int, src: int,
+               stream: int | None = None, tuning: ud_tuning | None = None) -> None:
+    """Enqueue ``table[idx[i], :] = src[i, :]``; all pointers are device addresses."""
+    if tuning is None:
+        _check(_lib.ud_scatter(table, N, D, dtype, idx, itype, M, src, stream), "ud_scatter")
+    else:
+        _check(_lib.ud_scatter_tuned(table, N, D, dtype, idx, itype, M, src, stream, ctypes.byref(tuning)), "ud_scatter_tuned")
 
 
 def ud_cache_create(table: int, hot_rows_host_ptr: int, n_hot: int) -> int:

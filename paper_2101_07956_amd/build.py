@@ -33,7 +33,7 @@ FLAGS = [
 
 LIBS = {
     "libud.so": ["ud_boundary.hip", "ud_gather_f32.hip", "ud_gather_f16.hip",
-                 "ud_gather_f16_to_f32.hip", "ud_gather_elementwise.hip"],
+                 "ud_gather_f16_to_f32.hip", "ud_gather_elementwise.hip", "ud_scatter.hip"],
     "libud_baseline.so": ["baseline_cpu_centric.hip"],
 }
 

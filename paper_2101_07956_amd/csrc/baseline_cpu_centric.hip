@@ -121,6 +121,37 @@ int udb_h2d_peak(size_t bytes, int reps, double *best_gbps, double *median_gbps)
     return 0;
 }
 
+// Same in the other direction: device -> pinned host.
+int udb_d2h_peak(size_t bytes, int reps, double *best_gbps, double *median_gbps)
+{
+    void *h = nullptr, *d = nullptr;
+    if (hipHostMalloc(&h, bytes, hipHostMallocDefault) != hipSuccess)
+        return 1;
+    if (hipMalloc(&d, bytes) != hipSuccess) {
+        (void)hipHostFree(h);
+        return 1;
+    }
+    (void)hipMemset(d, 1, bytes);
+    (void)hipMemcpy(h, d, bytes, hipMemcpyDeviceToHost); // warm-up
+    std::vector<double> rates;
+    for (int r = 0; r < reps; ++r) {
+        (void)hipDeviceSynchronize();
+        const auto t0 = clk::now();
+        if (hipMemcpy(h, d, bytes, hipMemcpyDeviceToHost) != hipSuccess)
+            break;
+        (void)hipDeviceSynchronize();
+        rates.push_back(static_cast<double>(bytes) / seconds_since(t0) / 1e9);
+    }
+    (void)hipFree(d);
+    (void)hipHostFree(h);
+    if (rates.empty())
+        return 2;
+    std::sort(rates.begin(), rates.end());
+    *best_gbps = rates.back();
+    *median_gbps = rates[rates.size() / 2];
+    return 0;
+}
+
 // Same for device -> device copies; the rate counts bytes copied once (the
 // HBM traffic is twice that: one read and one write).
 int udb_d2d_peak(size_t bytes, int reps, double *best_gbps, double *median_gbps)

@@ -370,6 +370,76 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
     return gather_impl(table, N, D, dtype, idx, itype, M, out, stream, nullptr, nullptr, nullptr);
 }
 
+ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
+                           const void *idx, ud_itype itype, int64_t M,
+                           const void *src, void *stream, const ud_tuning *tuning)
+{
+    if (N < 1 || D < 1 || M < 0)
+        return UD_ERR_INVALID_ARG;
+    if (dtype != UD_F32 && dtype != UD_F16)
+        return UD_ERR_INVALID_ARG;
+    if (itype != UD_I64 && itype != UD_I32)
+        return UD_ERR_INVALID_ARG;
+    int64_t table_bytes, src_bytes;
+    if (mul3_overflows(N, D, elem_bytes(dtype), &table_bytes) || mul3_overflows(M, D, elem_bytes(dtype), &src_bytes))
+        return UD_ERR_INVALID_ARG;
+    if (table_bytes > INT64_MAX - 64)
+        return UD_ERR_INVALID_ARG;
+    ud::Plan plan = auto_plan(table, D, dtype);
+    plan.flags = 0;
+    if (tuning) {
+        if (tuning->flags)
+            return UD_ERR_INVALID_ARG;
+        if (tuning->lanes_per_row < 0 || tuning->lanes_per_row > 64 ||
+            (tuning->lanes_per_row && !is_pow2(tuning->lanes_per_row)))
+            return UD_ERR_INVALID_ARG;
+        if (tuning->chunks_per_lane < 0 || tuning->chunks_per_lane > 4 || tuning->rows_in_flight < 0 ||
+            tuning->max_blocks < 0)
+            return UD_ERR_INVALID_ARG;
+        if (tuning->lanes_per_row)
+            plan.lanes_per_row = tuning->lanes_per_row;
+        if (tuning->chunks_per_lane)
+            plan.chunks_per_lane = tuning->chunks_per_lane;
+        if (tuning->rows_in_flight)
+            plan.rows_in_flight = tuning->rows_in_flight;
+        else if (tuning->chunks_per_lane)
+            plan.rows_in_flight = 1;
+        if (tuning->max_blocks)
+            plan.max_blocks = tuning->max_blocks;
+    }
+    if (M == 0)
+        return UD_OK;
+    if (!table || !idx || !src)
+        return UD_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(table) % elem_bytes(dtype) || reinterpret_cast<uintptr_t>(src) % elem_bytes(dtype) ||
+        reinterpret_cast<uintptr_t>(idx) % (itype == UD_I64 ? 8 : 4))
+        return UD_ERR_INVALID_ARG;
+    ud::GatherArgs a{};
+    a.table = static_cast<const char *>(table);
+    a.N = N;
+    a.D = D;
+    a.idx = idx;
+    a.itype = itype;
+    a.M = M;
+    a.out = const_cast<void *>(src);
+    const ud_status es = error_word(&a.err);
+    if (es != UD_OK)
+        return es;
+    const hipError_t e = ud::launch_scatter(a, elem_bytes(dtype), plan, static_cast<hipStream_t>(stream));
+    if (e == hipErrorInvalidValue)
+        return UD_ERR_UNSUPPORTED;
+    if (e != hipSuccess)
+        return hip_fail(e, "kernel launch");
+    return UD_OK;
+}
+
+ud_status ud_scatter(void *table, int64_t N, int64_t D, ud_dtype dtype,
+                     const void *idx, ud_itype itype, int64_t M,
+                     const void *src, void *stream)
+{
+    return ud_scatter_tuned(table, N, D, dtype, idx, itype, M, src, stream, nullptr);
+}
+
 ud_status ud_cache_create(const ud_table *table, const int64_t *hot_rows, int64_t n_hot, ud_cache **c)
 {
     if (!table || !c || table->device_resident || n_hot < 1 || n_hot > table->N || n_hot > INT32_MAX || !hot_rows)

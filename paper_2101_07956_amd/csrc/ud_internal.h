@@ -47,6 +47,10 @@ hipError_t launch_chunked_f16_to_f32(const GatherArgs &a, const Plan &p, hipStre
 // slot[rows[k]] = k for k < n (building a hot-row cache's map).
 hipError_t launch_fill_slots(const int64_t *rows, int64_t n, int32_t *slot, hipStream_t s);
 
+// Enqueue the chunked scatter table[idx[i], :] = src[i, :]; a.out is the dense
+// source, a.table the destination.  elem_bytes is 4 or 2.
+hipError_t launch_scatter(const GatherArgs &a, int elem_bytes, const Plan &p, hipStream_t s);
+
 // Enqueue the one-lane-per-element gather.
 hipError_t launch_elementwise(const GatherArgs &a, int dtype, const Plan &p, hipStream_t s);
 

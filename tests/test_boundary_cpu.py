@@ -58,6 +58,19 @@ def test_gather_rejects_bad_scalars_before_any_device_work(ud):
     assert _gather(ud, M=2**40, D=2**30, N=4) == inv
 
 
+def test_scatter_rejects_bad_arguments(ud):
+    inv = ud.UD_ERR_INVALID_ARG
+    rs = ud.binding.raw_status
+    ok_args = [0x1000, 10, 4, 0, 0x2000, 0, 5, 0x3000, None]
+    for pos, val in ((1, 0), (2, 0), (6, -1), (3, 2), (3, 7), (5, 3), (0, None), (4, None), (7, None), (0, 0x1002), (7, 0x3001)):
+        a = list(ok_args)
+        a[pos] = val
+        assert rs("ud_scatter", *a) == inv, (pos, val)
+    a = list(ok_args)
+    a[6] = 0
+    assert rs("ud_scatter", *a) == ud.UD_OK                 # M == 0: no-op, no device needed
+
+
 def test_empty_gather_is_ok_without_a_device(ud):
     assert _gather(ud, M=0, table=None, idx=None, out=None) == ud.UD_OK
 

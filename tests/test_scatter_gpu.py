@@ -1,0 +1,154 @@
+"""GPU parity of the write direction (ud_scatter) against the oracle, bit for bit."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ud():
+    import paper_2101_07956_amd as m
+    return m
+
+
+def distinct_ids(seed, M, N, dtype=np.int64):
+    return np.random.default_rng(seed).permutation(N)[:M].astype(dtype)
+
+
+def run_scatter(ud, table, idx_np, src_np, tuning=None):
+    dtype = ud.UD_F32 if src_np.dtype.itemsize == 4 else ud.UD_F16
+    idx = torch.from_numpy(idx_np).cuda()
+    src = torch.from_numpy(src_np.view(np.int32 if src_np.dtype.itemsize == 4 else np.int16)).cuda()
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_scatter(table.device_ptr, table.N, table.D, dtype, idx.data_ptr(),
+                  ud.UD_I64 if idx_np.dtype == np.int64 else ud.UD_I32, idx_np.size, src.data_ptr(), s, tuning)
+    ud.ud_gather_status(s)
+
+
+def bits(a):
+    return a.view(np.uint32 if a.dtype.itemsize == 4 else np.uint16)
+
+
+@pytest.mark.parametrize("D", [1, 3, 4, 5, 16, 64, 100, 127, 128, 129, 256, 513, 602, 603, 1031, 4099])
+def test_f32_scatter_into_host_table(ud, D):
+    N, M = 3001, 1777
+    t = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_uniform_f32(t.host_ptr, 500 + D, N * D)
+    want = t.numpy().copy()
+    for idt in (np.int64, np.int32):
+        idx = distinct_ids(D, M, N, idt)
+        if 0 not in idx and N - 1 not in idx:
+            idx[:2] = [0, N - 1]                       # first and last table row: head/tail chunks at the table's ends
+        src = workloads.uniform_f32(600 + D, M, D)
+        run_scatter(ud, t, idx, src)
+        oracle.scatter(want, idx, src)
+        assert np.array_equal(bits(t.numpy()), bits(want)), (D, idt)
+    t.free()
+
+
+@pytest.mark.parametrize("D", [1, 3, 8, 9, 301, 602, 603])
+def test_f16_scatter_into_host_table(ud, D):
+    N, M = 2503, 1200
+    t = ud.Table(N, D, ud.UD_F16)
+    workloads.fill_normal_f16(t.host_ptr, 700 + D, N * D)
+    want = t.numpy().copy()
+    idx = distinct_ids(D, M, N, np.int32)
+    src = workloads.normal_f16(800 + D, M, D)
+    run_scatter(ud, t, idx, src)
+    oracle.scatter(want, idx, src)
+    assert np.array_equal(bits(t.numpy()), bits(want)), D
+    t.free()
+
+
+PLANS = [(1, 1), (2, 1), (4, 1), (1, 2), (2, 2), (1, 3), (1, 4)]
+
+
+@pytest.mark.parametrize("u,p", PLANS)
+def test_every_scatter_instantiation_and_group_size(ud, u, p):
+    N, M = 1201, 900
+    for elem, D in ((ud.UD_F32, 77), (ud.UD_F16, 75)):
+        t = ud.Table(N, D, elem)
+        for lanes in (1, 4, 16, 64):
+            fill = workloads.uniform_f32 if elem == ud.UD_F32 else workloads.normal_f16
+            t.numpy()[:] = fill(1, N, D)
+            want = t.numpy().copy()
+            idx = distinct_ids(lanes + u * 10 + p, M, N)
+            src = fill(2 + lanes, M, D)
+            run_scatter(ud, t, idx, src, ud.ud_tuning(lanes, p, u, 0, 0))
+            oracle.scatter(want, idx, src)
+            assert np.array_equal(bits(t.numpy()), bits(want)), (elem, lanes, u, p)
+        t.free()
+
+
+def test_scatter_into_hbm_table_then_gather_back(ud):
+    N, D, M = 20_000, 100, 7001
+    host = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_uniform_f32(host.host_ptr, 9, N * D)
+    dev = host.to_device()
+    idx = distinct_ids(10, M, N)
+    src = workloads.uniform_f32(11, M, D)
+    run_scatter(ud, dev, idx, src)
+    want = host.numpy().copy()
+    oracle.scatter(want, idx, src)
+    # read the whole HBM table back with the gather
+    allrows = torch.arange(N, dtype=torch.int64, device="cuda")
+    out = torch.empty((N, D), dtype=torch.float32, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_gather(dev.device_ptr, N, D, ud.UD_F32, allrows.data_ptr(), ud.UD_I64, N, out.data_ptr(), s)
+    ud.ud_gather_status(s)
+    assert np.array_equal(bits(out.cpu().numpy()), bits(want))
+    dev.free()
+    host.free()
+
+
+def test_duplicate_ids_leave_one_of_the_candidates_per_element(ud):
+    N, D, M = 50, 100, 400                                       # every row is hit about 8 times
+    t = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_uniform_f32(t.host_ptr, 12, N * D)
+    before = t.numpy().copy()
+    idx = workloads.indices_uniform(13, M, N)
+    src = workloads.uniform_f32(14, M, D)
+    run_scatter(ud, t, idx, src)
+    after = t.numpy()
+    for r in range(N):
+        cand = src[idx == r]
+        if cand.shape[0] == 0:
+            assert np.array_equal(after[r], before[r])
+        else:
+            assert (after[r][None, :] == cand).any(axis=0).all(), r
+    t.free()
+
+
+def test_bad_ids_are_skipped_and_reported(ud):
+    N, D, M = 300, 64, 200
+    t = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_uniform_f32(t.host_ptr, 15, N * D)
+    want = t.numpy().copy()
+    idx = distinct_ids(16, M, N)
+    src = workloads.uniform_f32(17, M, D)
+    bad = idx.copy()
+    bad[[150, 20]] = [N, -1]
+    with pytest.raises(ud.UdIndexError) as e:
+        run_scatter(ud, t, bad, src)
+    assert e.value.pos == 20
+    good = np.ones(M, dtype=bool)
+    good[[150, 20]] = False
+    oracle.scatter(want, np.ascontiguousarray(idx[good]), np.ascontiguousarray(src[good]))
+    assert np.array_equal(bits(t.numpy()), bits(want))       # rows with valid IDs written, nothing else touched
+    t.free()
+
+
+def test_empty_scatter(ud):
+    t = ud.Table(8, 8, ud.UD_F32)
+    workloads.fill_uniform_f32(t.host_ptr, 18, 64)
+    before = t.numpy().copy()
+    ud.ud_scatter(t.device_ptr, 8, 8, ud.UD_F32, None, ud.UD_I64, 0, None, None)
+    ud.ud_gather_status(None)
+    assert np.array_equal(t.numpy(), before)
+    t.free()
