@@ -439,8 +439,16 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
             return f
 
         variants = {}
-        for name, tun in (("auto", None), ("64_workgroups", ud.ud_tuning(0, 0, 0, 64, 0)),
-                          ("16_workgroups", ud.ud_tuning(0, 0, 0, 16, 0))):
+        for name, tun in (("auto_512wg", None), ("256wg", ud.ud_tuning(0, 0, 0, 256, 0)),
+                          ("128wg", ud.ud_tuning(0, 0, 0, 128, 0)), ("64wg", ud.ud_tuning(0, 0, 0, 64, 0)),
+                          ("64wg_4rows_in_flight", ud.ud_tuning(0, 1, 4, 64, 0)),
+                          ("32wg_4rows_in_flight", ud.ud_tuning(0, 1, 4, 32, 0)),
+                          ("128wg_priority", ud.ud_tuning(0, 0, 0, 128, ud.UD_TUNE_WAVE_PRIORITY)),
+                          ("32wg_of_1024", ud.ud_tuning(0, 0, 0, 32, ud.UD_TUNE_BIG_BLOCKS)),
+                          ("16wg_of_1024", ud.ud_tuning(0, 0, 0, 16, ud.UD_TUNE_BIG_BLOCKS)),
+                          ("16wg_of_1024_2rows", ud.ud_tuning(0, 1, 2, 16, ud.UD_TUNE_BIG_BLOCKS)),
+                          ("8wg_of_1024_2rows", ud.ud_tuning(0, 1, 2, 8, ud.UD_TUNE_BIG_BLOCKS)),
+                          ("8wg_of_1024_4rows", ud.ud_tuning(0, 1, 4, 8, ud.UD_TUNE_BIG_BLOCKS))):
             tg = timed(only_gather(tun)) / nb
             ts = timed(serial(tun)) / nb
             to = timed(overlapped(tun)) / nb

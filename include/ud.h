@@ -153,7 +153,8 @@ ud_status ud_gather_cached(const ud_cache *c, ud_dtype dtype, const void *idx, u
  * Kernel tuning for ud_gather_tuned; a zero field means "choose automatically".
  *   lanes_per_row    power of two in [1, 64]: lanes of a wavefront that share one row
  *   chunks_per_lane  1..4: 16-byte chunks of one row each lane keeps in flight
- *   rows_in_flight   1, 2, 4 or 8: rows each lane group loads before storing any
+ *   rows_in_flight   1, 2 or 4: rows each lane group loads before storing any
+ *                    (rows_in_flight x chunks_per_lane <= 8; 4 x 2 is not built)
  *   max_blocks       cap on workgroups (grid-stride beyond it)
  *   flags            UD_TUNE_* bits
  */
@@ -168,6 +169,11 @@ typedef struct {
 enum {
     UD_TUNE_NT_LOAD = 1u,       /* non-temporal (streaming) loads from the table */
     UD_TUNE_NT_STORE = 2u,      /* non-temporal stores to out */
+    UD_TUNE_WAVE_PRIORITY = 8u, /* raise the gather wavefronts' issue priority (s_setprio): for gathers that
+                                   share the GPU with a compute kernel on another stream */
+    UD_TUNE_BIG_BLOCKS = 16u,   /* 1024-thread workgroups instead of 256: with a small max_blocks the whole
+                                   gather then sits on few compute units and leaves the others, registers
+                                   included, to a compute kernel running beside it */
     UD_TUNE_ELEMENTWISE = 4u    /* one lane per element, rows straddling wavefronts: the layout of
                                    the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
                                    the comparison point and as the fallback for odd alignments */

@@ -290,7 +290,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
 
     ud::Plan plan = auto_plan(table, D, dtype);
     if (tuning) {
-        if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE))
+        if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_WAVE_PRIORITY | UD_TUNE_BIG_BLOCKS))
             return UD_ERR_INVALID_ARG;
         if (tuning->lanes_per_row < 0 || tuning->lanes_per_row > 64 ||
             (tuning->lanes_per_row && !is_pow2(tuning->lanes_per_row)))
@@ -298,7 +298,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
         if (tuning->chunks_per_lane < 0 || tuning->chunks_per_lane > 4)
             return UD_ERR_INVALID_ARG;
         const int u = tuning->rows_in_flight;
-        if (u != 0 && u != 1 && u != 2 && u != 4 && u != 8)
+        if (u != 0 && u != 1 && u != 2 && u != 4)
             return UD_ERR_INVALID_ARG;
         if (tuning->max_blocks < 0)
             return UD_ERR_INVALID_ARG;
@@ -313,7 +313,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
             plan.rows_in_flight = 1;
         if (tuning->max_blocks)
             plan.max_blocks = tuning->max_blocks;
-        if (plan.rows_in_flight * plan.chunks_per_lane > 8)
+        if (plan.rows_in_flight * plan.chunks_per_lane > 8 || (plan.rows_in_flight == 4 && plan.chunks_per_lane == 2))
             return UD_ERR_UNSUPPORTED;
     }
 
@@ -335,6 +335,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
     a.out = out;
     a.slot = slot;
     a.cache = cache;
+    a.high_priority = (plan.flags & UD_TUNE_WAVE_PRIORITY) ? 1 : 0;
     const ud_status es = error_word(&a.err);
     if (es != UD_OK)
         return es;

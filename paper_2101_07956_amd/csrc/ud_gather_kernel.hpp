@@ -142,19 +142,25 @@ __device__ __forceinline__ void store_halves(uint16_t *d, u32x4 v, int lo, int h
 
 // DT: UD_F32 / UD_F16 / UD_F16_TO_F32.  U rows in flight per lane group, P
 // chunks per lane per row.  lg = log2(lanes per row).
+// Workgroups are 256 threads by default and 1024 on request (all waves of a
+// workgroup share a compute unit, so few large workgroups keep the gather on few
+// compute units): the launch bound is the larger of the two.
 template <int DT, int U, int P, bool NTL, bool NTS>
-__global__ __launch_bounds__(kBlockThreads) void gather_chunked(GatherArgs a, int lg)
+__global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a, int lg)
 {
     constexpr int IN_ESZ = (DT == UD_F32) ? 4 : 2;      // table element bytes
     constexpr int EPC = 16 / IN_ESZ;                    // elements per 16-byte chunk
+    if (a.high_priority)
+        __builtin_amdgcn_s_setprio(3);                  // issue ahead of a co-running compute kernel's waves
     const int lane = threadIdx.x & 63;
     const int lpr = 1 << lg;
     const int grp = lane >> lg;                         // which row of the wavefront's batch
     const int l = lane & (lpr - 1);                     // which chunk slot of that row
     const int rpw = 64 >> lg;                           // rows per wavefront per pass
     const int64_t rows_per_iter = static_cast<int64_t>(rpw) * U;
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
-    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
+    const int waves_per_block = blockDim.x >> 6;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * waves_per_block + (threadIdx.x >> 6);
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * waves_per_block;
     const int64_t row_bytes = a.D * IN_ESZ;
     // upper bound of chunks per row over all alignments; identical in every lane
     const int64_t span = static_cast<int64_t>(P) * lpr;
@@ -232,17 +238,17 @@ __global__ __launch_bounds__(kBlockThreads) void gather_chunked(GatherArgs a, in
 }
 
 template <int DT, int U, int P>
-hipError_t launch_nt(const GatherArgs &a, const Plan &p, int lg, dim3 grid, hipStream_t s)
+hipError_t launch_nt(const GatherArgs &a, const Plan &p, int lg, dim3 grid, dim3 block, hipStream_t s)
 {
     const bool ntl = p.flags & UD_TUNE_NT_LOAD, nts = p.flags & UD_TUNE_NT_STORE;
     if (ntl && nts)
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, true>), grid, dim3(kBlockThreads), 0, s, a, lg);
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, true>), grid, block, 0, s, a, lg);
     else if (ntl)
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, false>), grid, dim3(kBlockThreads), 0, s, a, lg);
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, false>), grid, block, 0, s, a, lg);
     else if (nts)
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, true>), grid, dim3(kBlockThreads), 0, s, a, lg);
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, true>), grid, block, 0, s, a, lg);
     else
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, false>), grid, dim3(kBlockThreads), 0, s, a, lg);
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, false>), grid, block, 0, s, a, lg);
     return hipGetLastError();
 }
 
@@ -257,24 +263,23 @@ hipError_t launch_chunked(const GatherArgs &a, const Plan &p, hipStream_t s)
         return hipErrorInvalidValue;
     const int64_t rows_per_wave = static_cast<int64_t>(64 >> lg) * p.rows_in_flight;
     const int64_t waves = (a.M + rows_per_wave - 1) / rows_per_wave;
-    int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int wpb = (p.flags & UD_TUNE_BIG_BLOCKS) ? kMaxBlockThreads / 64 : kWavesPerBlock;
+    int64_t blocks = (waves + wpb - 1) / wpb;
     if (blocks > p.max_blocks)
         blocks = p.max_blocks;
     if (blocks < 1)
         return hipSuccess;
-    const dim3 grid(static_cast<unsigned>(blocks));
+    const dim3 grid(static_cast<unsigned>(blocks)), block(static_cast<unsigned>(wpb * 64));
     const int key = p.rows_in_flight * 10 + p.chunks_per_lane;
     switch (key) {
 #define UD_CASE(U_, P_) \
     case U_ * 10 + P_:  \
-        return launch_nt<DT, U_, P_>(a, p, lg, grid, s);
+        return launch_nt<DT, U_, P_>(a, p, lg, grid, block, s);
         UD_CASE(1, 1)
         UD_CASE(2, 1)
         UD_CASE(4, 1)
-        UD_CASE(8, 1)
         UD_CASE(1, 2)
         UD_CASE(2, 2)
-        UD_CASE(4, 2)
         UD_CASE(1, 3)
         UD_CASE(2, 3)
         UD_CASE(1, 4)

@@ -23,6 +23,7 @@ struct GatherArgs {
     // from cache + slot[r] * row_bytes (HBM) instead of table + r * row_bytes
     const int32_t *slot;
     const char *cache;
+    int high_priority;       // nonzero: the kernel raises its wavefronts' issue priority
 };
 
 // Resolved kernel parameters (every field concrete, see ud_tuning).
@@ -37,6 +38,8 @@ struct Plan {
 // Wavefronts per workgroup used by every kernel here.
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;
+// Largest workgroup the chunked gather may be launched with (UD_TUNE_BIG_BLOCKS).
+constexpr int kMaxBlockThreads = 1024;
 
 // Enqueue the chunked (row-per-lane-group) gather.  Returns hipErrorInvalidValue
 // if (dtype, plan) has no instantiation.

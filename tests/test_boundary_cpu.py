@@ -83,9 +83,11 @@ def test_tuning_fields_are_range_checked(ud):
     assert _gather(ud, tuning=T(0, 5, 0, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 3, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, -1, 0)) == inv
-    assert _gather(ud, tuning=T(0, 0, 0, 0, 8)) == inv
-    assert _gather(ud, tuning=T(0, 4, 8, 0, 0)) == ud.UD_ERR_UNSUPPORTED   # no such instantiation
-    assert _gather(ud, M=0, tuning=T(64, 2, 4, 0, 3)) == ud.UD_OK
+    assert _gather(ud, tuning=T(0, 0, 0, 0, 32)) == inv
+    assert _gather(ud, tuning=T(0, 0, 8, 0, 0)) == inv
+    assert _gather(ud, tuning=T(0, 4, 4, 0, 0)) == ud.UD_ERR_UNSUPPORTED   # no such instantiation
+    assert _gather(ud, tuning=T(0, 2, 4, 0, 0)) == ud.UD_ERR_UNSUPPORTED
+    assert _gather(ud, M=0, tuning=T(64, 2, 2, 0, 3)) == ud.UD_OK
 
 
 def test_table_calls_reject_bad_arguments(ud):
