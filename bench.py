@@ -52,14 +52,14 @@ def _load_baseline_lib(ud):
     return bl
 
 
-def _read_traffic_note():
+def _read_traffic_note(key="traffic_bytes_per_launch"):
     """Fabric traffic (bytes per launch) of the dominant kernel, measured offline with rocprofv3 --pmc
     FETCH_SIZE / WRITE_SIZE and kept in the committed counter summary; None if that file is absent."""
     path = os.path.join(ROOT, "profiles", "gather_f32_D602_traffic.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
-        if line.startswith("traffic_bytes_per_launch="):
+        if line.startswith(key + "="):
             return float(line.split("=", 1)[1])
     return None
 
@@ -747,7 +747,12 @@ def main() -> int:
                      "ms_per_launch": round(dom_ms, 4)},
         "roofline_hbm": {"bound": "hbm", "kernel": "gather_chunked<f32> D=602, table in HBM",
                          "achieved": round(hbm_achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                         "frac": round(hbm_achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                         "frac": round(hbm_achieved / HBM_PEAK_GBPS, 4),
+                         "traffic": _read_traffic_note("hbm_variant_traffic_bytes_per_launch"),
+                         "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
+                         "algorithmic_bytes_per_launch": hbm_bytes_602,
+                         "per_width_GBps_read_plus_write": {str(D): round(M_ROWS * (2 * D * 4 + 8) / per_ms_hbm[D] / 1e6, 1)
+                                                            for D in WIDTHS},
                          "ms_per_launch": round(per_ms_hbm[602], 4),
                          "sweep_GBps_read_plus_write": round(K * 2 * bytes_per_step / elapsed_hbm / 1e9, 1),
                          "d2d_memcpy_traffic_GBps": round(2 * d2d_copy, 1)},
