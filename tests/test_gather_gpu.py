@@ -370,3 +370,40 @@ def test_cached_gather_fp16_and_errors(ud):
         ud.Cache(t, np.array([0, N], dtype=np.int64))
     c.free()
     t.free()
+
+
+def test_more_rows_than_the_workgroup_cap_and_offsets_beyond_32_bits(ud):
+    # 17,000,000 rows of 256 bytes: one wavefront per row would need more workgroups than the
+    # launch cap, so the kernel strides; output offsets pass 4 GiB
+    N, D, M = 200_000, 64, 17_000_000
+    t = make_table(ud, N, D, ud.UD_F32, 50)
+    idx = workloads.indices_uniform(51, M, N)
+    didx = torch.from_numpy(idx).cuda()
+    out = torch.empty(M * D + 16, dtype=torch.int32, device="cuda")
+    out[M * D:] = 0x5A5A5A5A
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, out.data_ptr(), s)
+    ud.ud_gather_status(s)
+    want = np.empty((M, D), dtype=np.uint32)
+    oracle.gather_raw(t.host_ptr, N, D, oracle.F32, idx, want)
+    host = out.cpu().numpy().view(np.uint32)
+    assert (host[M * D:] == 0x5A5A5A5A).all()
+    assert np.array_equal(host[: M * D].reshape(M, D), want)
+    t.free()
+
+
+def test_single_row_table_and_single_id(ud):
+    t = make_table(ud, 1, 602, ud.UD_F32, 52)
+    got = run_gather(ud, t, np.zeros(1, dtype=np.int64), ud.UD_F32)
+    assert np.array_equal(got, t.numpy().view(np.uint32))
+    got = run_gather(ud, t, np.zeros(333, dtype=np.int32), ud.UD_F32)
+    assert (got == t.numpy().view(np.uint32)).all()
+    t.free()
+
+
+def test_very_wide_rows(ud):
+    N, D, M = 37, 100_003, 29                  # 400 KB rows: many chunk blocks per row
+    t = make_table(ud, N, D, ud.UD_F32, 53)
+    idx = workloads.indices_uniform(54, M, N)
+    assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32), oracle_bits(t.numpy(), idx, oracle.F32))
+    t.free()
