@@ -64,6 +64,22 @@ def _read_traffic_note(key="traffic_bytes_per_launch"):
     return None
 
 
+def _host_topology():
+    """Sockets and NUMA nodes of the host, as far as /proc and /sys tell."""
+    info = {}
+    try:
+        phys = {line.split(":")[1].strip() for line in open("/proc/cpuinfo") if line.startswith("physical id")}
+        info["sockets"] = len(phys) or None
+        info["cpu_model"] = next((line.split(":", 1)[1].strip() for line in open("/proc/cpuinfo")
+                                  if line.startswith("model name")), None)
+        nodes = [d for d in os.listdir("/sys/devices/system/node") if d.startswith("node") and d[4:].isdigit()]
+        info["numa_nodes"] = len(nodes) or None
+        info["cpus_online"] = os.cpu_count()
+    except OSError:
+        pass
+    return info
+
+
 def _stats(ms):
     ms = sorted(ms)
     return {"median_ms": round(ms[len(ms) // 2], 4), "min_ms": round(ms[0], 4), "reps": len(ms)}
@@ -580,6 +596,9 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if not os.path.exists(os.path.join(ROOT, "paper_2101_07956_amd", "libud.so")):
+        from paper_2101_07956_amd import build as hip_build      # nothing built yet: build, else load what is there
+        hip_build.build(verbose=False)
     import paper_2101_07956_amd as ud
     import workloads
 
@@ -636,15 +655,19 @@ def main() -> int:
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         ud.ud_gather_status(stream)          # raises if any ID was out of range
-        per = {D: sum(a.elapsed_time(b) for a, b in ev) / len(ev) for D, ev in events.items()}   # ms per launch
+        raw = {D: [a.elapsed_time(b) for a, b in ev] for D, ev in events.items()}
+        per = {D: sum(v) / len(v) for D, v in raw.items()}                                       # mean ms per launch
+        timed.spread = {D: (sorted(v)[len(v) // 2], min(v)) for D, v in raw.items()}             # median, min
         return elapsed, per
 
     elapsed, per_ms = timed(table.device_ptr)
     bytes_per_step = sum(M_ROWS * D * 4 for D in WIDTHS)
     value = K * bytes_per_step / elapsed / 1e9
     rows_per_s = K * M_ROWS * len(WIDTHS) / elapsed
+    spread = dict(timed.spread)
     per_width = {
-        str(D): {"row_bytes": D * 4, "ms": round(per_ms[D], 4), "GBps": round(M_ROWS * D * 4 / per_ms[D] / 1e6, 2),
+        str(D): {"row_bytes": D * 4, "ms": round(per_ms[D], 4), "ms_median": round(spread[D][0], 4),
+                 "ms_min": round(spread[D][1], 4), "GBps": round(M_ROWS * D * 4 / per_ms[D] / 1e6, 2),
                  "frac_of_h2d_peak": round(M_ROWS * D * 4 / per_ms[D] / 1e6 / h2d_peak, 4),
                  "rows_per_s": round(M_ROWS / per_ms[D] * 1e3)}
         for D in WIDTHS
@@ -758,7 +781,7 @@ def main() -> int:
                          "d2d_memcpy_traffic_GBps": round(2 * d2d_copy, 1)},
         "cpu_baseline": cpu_baseline,
         "cpu_centric": cpu_centric,
-        "host": {"cores_visible": ncores, "device": torch.cuda.get_device_name(0)},
+        "host": {"cores_visible": ncores, "device": torch.cuda.get_device_name(0), **_host_topology()},
     }
     table.free()
     print(json.dumps(line))

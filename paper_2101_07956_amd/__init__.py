@@ -20,6 +20,8 @@ __all__ = ["binding", "table", "build"]
 def __getattr__(name: str):
     if name.startswith("__"):
         raise AttributeError(name)
+    if name in ("build", "tune", "binding", "table"):          # submodules: plain imports, no library needed for build
+        return importlib.import_module("." + name, __name__)
     binding = importlib.import_module(".binding", __name__)
     if hasattr(binding, name):
         return getattr(binding, name)

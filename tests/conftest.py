@@ -10,6 +10,17 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    _build_if_nothing_is_built()
+
+
+def _build_if_nothing_is_built():
+    """The tests load the in-tree libraries as built; only a tree with no library at all is built first
+    (hipcc cross-compiles without a GPU).  After changing a source, rebuild before running the tests."""
+    pkg = os.path.join(ROOT, "paper_2101_07956_amd")
+    if all(os.path.exists(os.path.join(pkg, lib)) for lib in ("libud.so", "libud_baseline.so")):
+        return
+    from paper_2101_07956_amd import build as hip_build
+    hip_build.build(verbose=False)
 
 
 def pytest_collection_modifyitems(config, items):
