@@ -174,6 +174,8 @@ enum {
     UD_TUNE_BIG_BLOCKS = 16u,   /* 1024-thread workgroups instead of 256: with a small max_blocks the whole
                                    gather then sits on few compute units and leaves the others, registers
                                    included, to a compute kernel running beside it */
+    UD_TUNE_CIRCULAR_SHIFT = 32u, /* with UD_TUNE_ELEMENTWISE: rotate each row's lanes as in Section 4.5 / Figure 5 of
+                                   the paper (its alignment fix), for comparison */
     UD_TUNE_ELEMENTWISE = 4u    /* one lane per element, rows straddling wavefronts: the layout of
                                    the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
                                    the comparison point and as the fallback for odd alignments */

@@ -290,7 +290,10 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
 
     ud::Plan plan = auto_plan(table, D, dtype);
     if (tuning) {
-        if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_WAVE_PRIORITY | UD_TUNE_BIG_BLOCKS))
+        if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_WAVE_PRIORITY | UD_TUNE_BIG_BLOCKS |
+                              UD_TUNE_CIRCULAR_SHIFT))
+            return UD_ERR_INVALID_ARG;
+        if ((tuning->flags & UD_TUNE_CIRCULAR_SHIFT) && !(tuning->flags & UD_TUNE_ELEMENTWISE))
             return UD_ERR_INVALID_ARG;
         if (tuning->lanes_per_row < 0 || tuning->lanes_per_row > 64 ||
             (tuning->lanes_per_row && !is_pow2(tuning->lanes_per_row)))

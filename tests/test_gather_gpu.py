@@ -139,8 +139,22 @@ def test_elementwise_kernel(ud, dtype_name, elem_name, D):
     N, M = 777, 1500
     t = make_table(ud, N, D, elem, 6)
     idx = workloads.indices_uniform(11, M, N, np.int32)
+    want = oracle_bits(t.numpy(), idx, dtype)
     got = run_gather(ud, t, idx, dtype, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE))
-    assert np.array_equal(got, oracle_bits(t.numpy(), idx, dtype))
+    assert np.array_equal(got, want)
+    # the paper's circular shift changes which lane moves which element, never the result
+    got = run_gather(ud, t, idx, dtype, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE | ud.UD_TUNE_CIRCULAR_SHIFT))
+    assert np.array_equal(got, want)
+    t.free()
+
+
+@pytest.mark.parametrize("D", [1, 3, 11, 63, 64, 65, 100, 513, 602])
+def test_circular_shift_kernel_widths(ud, D):
+    N, M = 1501, 2203
+    t = make_table(ud, N, D, ud.UD_F32, 700 + D)
+    idx = workloads.indices_uniform(12, M, N)
+    got = run_gather(ud, t, idx, ud.UD_F32, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE | ud.UD_TUNE_CIRCULAR_SHIFT))
+    assert np.array_equal(got, oracle_bits(t.numpy(), idx, oracle.F32)), D
     t.free()
 
 
