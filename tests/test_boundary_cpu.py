@@ -124,3 +124,14 @@ def test_plan_follows_row_width(ud):
     # rows that start at 4 different offsets modulo 16 can overlap one more chunk
     p = ud.ud_gather_plan(0x10000, 255, ud.UD_F32)      # 1020-byte rows: up to 65 chunks
     assert (p.lanes_per_row, p.chunks_per_lane) == (64, 2)
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(ud, tmp_path):
+    import subprocess
+    exe = str(tmp_path / "c_abi_check")
+    pkg = os.path.dirname(ud.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                           "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "c_abi_check.c"),
+                           "-o", exe, "-L", pkg, "-lud", "-Wl,-rpath," + pkg])
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and "c abi ok" in r.stdout, (r.returncode, r.stdout, r.stderr)

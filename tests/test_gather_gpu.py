@@ -421,3 +421,68 @@ def test_very_wide_rows(ud):
     idx = workloads.indices_uniform(54, M, N)
     assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32), oracle_bits(t.numpy(), idx, oracle.F32))
     t.free()
+
+
+def test_id_list_may_live_in_pinned_host_memory(ud):
+    # ud_gather needs device-dereferenceable pointers only: the ID list itself can stay in mapped host memory
+    N, D, M = 10_000, 128, 6001
+    t = make_table(ud, N, D, ud.UD_F32, 60)
+    ids_mem = ud.Table(1, 2 * M, ud.UD_F32)                       # M int64 slots of mapped host memory
+    idx = workloads.indices_uniform(61, M, N)
+    ids_mem.numpy().view(np.int64)[0, :] = idx
+    out = torch.empty((M, D), dtype=torch.float32, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, ids_mem.device_ptr, ud.UD_I64, M, out.data_ptr(), s)
+    ud.ud_gather_status(s)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), oracle_bits(t.numpy(), idx, oracle.F32))
+    ids_mem.free()
+    t.free()
+
+
+def test_two_streams_gather_concurrently(ud):
+    N, D, M = 50_000, 256, 40_000
+    t = make_table(ud, N, D, ud.UD_F32, 62)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    idxs = [workloads.indices_uniform(63 + k, M, N) for k in range(2)]
+    didx = [torch.from_numpy(a).cuda() for a in idxs]
+    outs = [torch.empty((M, D), dtype=torch.float32, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for k in range(2):
+            ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, didx[k].data_ptr(), ud.UD_I64, M, outs[k].data_ptr(),
+                         streams[k].cuda_stream)
+    for k in range(2):
+        ud.ud_gather_status(streams[k].cuda_stream)
+        assert np.array_equal(outs[k].cpu().numpy().view(np.uint32), oracle_bits(t.numpy(), idxs[k], oracle.F32))
+    t.free()
+
+
+def test_gathers_captured_in_a_hip_graph_replay_correctly(ud):
+    # a launch-bound inner loop (several small gathers) captured once and replayed with new IDs each time;
+    # the first eager call is what allocates the library's error word, so it runs before capture
+    N, M = 20_000, 3001
+    widths = (16, 100, 602)
+    t = make_table(ud, N, 602, ud.UD_F32, 64)
+    didx = torch.zeros(M, dtype=torch.int64, device="cuda")
+    outs = {D: torch.zeros((M, D), dtype=torch.float32, device="cuda") for D in widths}
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for D in widths:                                           # eager warm-up on the capture stream
+            ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, outs[D].data_ptr(), side.cuda_stream)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        cs = torch.cuda.current_stream().cuda_stream
+        for D in widths:
+            ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, outs[D].data_ptr(), cs)
+    for rep in range(4):
+        idx = workloads.indices_uniform(65 + rep, M, N)
+        didx.copy_(torch.from_numpy(idx))
+        torch.cuda.synchronize()                                   # the program's own eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        ud.ud_gather_status(None)
+        for D in widths:
+            view = np.ascontiguousarray(t.numpy().ravel()[: N * D].reshape(N, D))
+            assert np.array_equal(outs[D].cpu().numpy().view(np.uint32), oracle_bits(view, idx, oracle.F32)), (rep, D)
+    t.free()
