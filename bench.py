@@ -460,19 +460,29 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                         consume(bufs[b & 1])
             return f
 
+        spans = {}
+
         def overlapped(tun):
             def f():
-                g_done = [torch.cuda.Event() for _ in range(nb)]
-                c_done = [torch.cuda.Event() for _ in range(nb)]
+                g_start = [torch.cuda.Event(enable_timing=True) for _ in range(nb)]
+                g_done = [torch.cuda.Event(enable_timing=True) for _ in range(nb)]
+                c_start = [torch.cuda.Event(enable_timing=True) for _ in range(nb)]
+                c_done = [torch.cuda.Event(enable_timing=True) for _ in range(nb)]
                 for b in range(nb):
                     if b >= 2:
                         sg.wait_event(c_done[b - 2])            # buffer b&1 is free again
+                    g_start[b].record(sg)
                     gather_on(sg, b, bufs[b & 1], tun)
                     g_done[b].record(sg)
                     sc.wait_event(g_done[b])
+                    c_start[b].record(sc)
                     with torch.cuda.stream(sc):
                         consume(bufs[b & 1])
                     c_done[b].record(sc)
+                torch.cuda.synchronize()
+                mid = range(2, nb - 1)                          # steady state
+                spans["gather"] = sum(g_start[b].elapsed_time(g_done[b]) for b in mid) / len(mid)
+                spans["compute"] = sum(c_start[b].elapsed_time(c_done[b]) for b in mid) / len(mid)
             return f
 
         variants = {}
@@ -490,6 +500,8 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
             ts = timed(serial(tun)) / nb
             to = timed(overlapped(tun)) / nb
             variants[name] = {"gather_only_ms": round(tg, 3), "serial_ms": round(ts, 3), "overlapped_ms": round(to, 3),
+                              "gather_ms_while_overlapped": round(spans["gather"], 3),
+                              "compute_ms_while_overlapped": round(spans["compute"], 3),
                               "exposed_gather_ms": round(max(to - t_c, 0.0), 3),
                               "hidden_fraction_of_gather": round(1.0 - max(to - t_c, 0.0) / tg, 3)}
         ud.ud_gather_status(sg.cuda_stream)

@@ -486,3 +486,4 @@ def test_gathers_captured_in_a_hip_graph_replay_correctly(ud):
             view = np.ascontiguousarray(t.numpy().ravel()[: N * D].reshape(N, D))
             assert np.array_equal(outs[D].cpu().numpy().view(np.uint32), oracle_bits(view, idx, oracle.F32)), (rep, D)
     t.free()
+
