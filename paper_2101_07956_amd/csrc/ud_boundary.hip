@@ -128,8 +128,8 @@ bool table_is_in_hbm(const void *table)
 
 // Launch shape by row width and table residence, from sweeps on MI355X:
 //  * host table (link-bound): one row per wavefront instruction (64 lanes per
-//    row) as soon as a row spans at least two 128-byte lines, a single row in
-//    flight per lane group.  Whole-wave loads of one row reach 99-100% of the
+//    row) for every row longer than 64 bytes, a single row in flight per lane
+//    group.  Whole-wave loads of one row reach 99-100% of the
 //    pinned-memcpy rate for 256..1024-byte rows; packing several short rows
 //    into one instruction costs 3-5%.  From 1 KiB rows up a fixed grid of 512
 //    workgroups striding over the rows is 1-3% faster than one wavefront per
@@ -145,7 +145,7 @@ ud::Plan auto_plan(const void *table, int64_t D, ud_dtype dtype)
     p.flags = hbm ? UD_TUNE_NT_STORE : 0u;
     p.max_blocks = kDefaultMaxBlocks;
     if (nch <= 64) {
-        p.lanes_per_row = (!hbm && row_bytes >= 256) ? 64 : next_pow2(nch);
+        p.lanes_per_row = (!hbm && row_bytes > 64) ? 64 : next_pow2(nch);
         p.chunks_per_lane = 1;
         p.rows_in_flight = hbm ? 2 : 1;
     } else {

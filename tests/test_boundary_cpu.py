@@ -113,8 +113,8 @@ def test_table_calls_reject_bad_arguments(ud):
 
 def test_plan_follows_row_width(ud):
     # an address the runtime does not know counts as host memory: one row per wavefront
-    # instruction from 256-byte rows up, natural group size below
-    for D, lanes, chunks in [(16, 4, 1), (32, 8, 1), (64, 64, 1), (100, 64, 1), (128, 64, 1), (256, 64, 1),
+    # instruction for rows longer than 64 bytes, natural group size below
+    for D, lanes, chunks in [(16, 4, 1), (24, 64, 1), (32, 64, 1), (64, 64, 1), (100, 64, 1), (128, 64, 1), (256, 64, 1),
                              (602, 64, 3), (4096, 64, 4)]:
         p = ud.ud_gather_plan(0x10000, D, ud.UD_F32)
         assert (p.lanes_per_row, p.chunks_per_lane) == (lanes, chunks), D
