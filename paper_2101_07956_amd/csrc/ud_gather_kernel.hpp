@@ -24,7 +24,10 @@
 //     by word.
 //
 // Lane groups: lanes_per_row = 2^lg lanes share a row, 64 >> lg rows per
-// wavefront instruction.  Short rows get small groups so that no lane idles.
+// wavefront instruction.  Which group size is best depends on what bounds the
+// gather: an HBM-resident table wants no idle lanes (small groups for short
+// rows), a host-resident one is fastest with one row per wavefront instruction
+// even when most lanes idle; the choice is made on the host (ud_boundary.hip).
 #pragma once
 
 #include <hip/hip_runtime.h>

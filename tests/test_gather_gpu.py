@@ -487,3 +487,29 @@ def test_gathers_captured_in_a_hip_graph_replay_correctly(ud):
             assert np.array_equal(outs[D].cpu().numpy().view(np.uint32), oracle_bits(view, idx, oracle.F32)), (rep, D)
     t.free()
 
+
+
+@pytest.mark.parametrize("D", [1, 3, 16, 25, 100, 129, 602, 1031])
+def test_device_resident_table_widths(ud, D):
+    # the HBM-resident plan differs (small lane groups, two rows in flight, streaming stores)
+    N, M = 4001, 3777
+    host = make_table(ud, N, D, ud.UD_F32, 900 + D)
+    dev = host.to_device()
+    idx = workloads.indices_uniform(90, M, N)
+    idx[:2] = [0, N - 1]
+    got = run_gather(ud, dev, idx, ud.UD_F32, out_offset_elems=D % 4)
+    assert np.array_equal(got, oracle_bits(host.numpy(), idx, oracle.F32)), D
+    dev.free()
+    host.free()
+
+
+@pytest.mark.parametrize("D", [3, 301, 602])
+def test_device_resident_fp16_table(ud, D):
+    N, M = 3001, 2500
+    host = make_table(ud, N, D, ud.UD_F16, 950 + D)
+    dev = host.to_device()
+    idx = workloads.indices_uniform(91, M, N, np.int32)
+    for dtype in (ud.UD_F16, ud.UD_F16_TO_F32):
+        assert np.array_equal(run_gather(ud, dev, idx, dtype), oracle_bits(host.numpy(), idx, dtype)), (D, dtype)
+    dev.free()
+    host.free()
