@@ -176,6 +176,8 @@ enum {
                                    included, to a compute kernel running beside it */
     UD_TUNE_CIRCULAR_SHIFT = 32u, /* with UD_TUNE_ELEMENTWISE: rotate each row's lanes as in Section 4.5 / Figure 5 of
                                    the paper (its alignment fix), for comparison */
+    UD_TUNE_XCD_REMAP = 64u,    /* renumber workgroups so that each of the 8 XCDs (each with its own L2) serves one
+                                   contiguous range of output rows */
     UD_TUNE_ELEMENTWISE = 4u    /* one lane per element, rows straddling wavefronts: the layout of
                                    the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
                                    the comparison point and as the fallback for odd alignments */

@@ -291,7 +291,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
     ud::Plan plan = auto_plan(table, D, dtype);
     if (tuning) {
         if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_WAVE_PRIORITY | UD_TUNE_BIG_BLOCKS |
-                              UD_TUNE_CIRCULAR_SHIFT))
+                              UD_TUNE_CIRCULAR_SHIFT | UD_TUNE_XCD_REMAP))
             return UD_ERR_INVALID_ARG;
         if ((tuning->flags & UD_TUNE_CIRCULAR_SHIFT) && !(tuning->flags & UD_TUNE_ELEMENTWISE))
             return UD_ERR_INVALID_ARG;
@@ -339,6 +339,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
     a.slot = slot;
     a.cache = cache;
     a.high_priority = (plan.flags & UD_TUNE_WAVE_PRIORITY) ? 1 : 0;
+    a.xcd_remap = (plan.flags & UD_TUNE_XCD_REMAP) ? 1 : 0;
     const ud_status es = error_word(&a.err);
     if (es != UD_OK)
         return es;

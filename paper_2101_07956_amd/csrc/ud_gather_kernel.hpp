@@ -162,7 +162,14 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
     const int rpw = 64 >> lg;                           // rows per wavefront per pass
     const int64_t rows_per_iter = static_cast<int64_t>(rpw) * U;
     const int waves_per_block = blockDim.x >> 6;
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * waves_per_block + (threadIdx.x >> 6);
+    // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  With the
+    // remap each XCD serves one contiguous eighth of the output rows, so that neighbouring rows --
+    // which share ID-list lines and, for widths that are no multiple of 128 bytes, output lines --
+    // meet in the same L2.  The host rounds the grid up to a multiple of 8 for this.
+    int64_t block = blockIdx.x;
+    if (a.xcd_remap)
+        block = static_cast<int64_t>(blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int64_t wave = block * waves_per_block + (threadIdx.x >> 6);
     const int64_t nwaves = static_cast<int64_t>(gridDim.x) * waves_per_block;
     const int64_t row_bytes = a.D * IN_ESZ;
     // upper bound of chunks per row over all alignments; identical in every lane
@@ -272,6 +279,8 @@ hipError_t launch_chunked(const GatherArgs &a, const Plan &p, hipStream_t s)
         blocks = p.max_blocks;
     if (blocks < 1)
         return hipSuccess;
+    if (a.xcd_remap)
+        blocks = (blocks + 7) & ~static_cast<int64_t>(7);      // surplus wavefronts find no rows and exit
     const dim3 grid(static_cast<unsigned>(blocks)), block(static_cast<unsigned>(wpb * 64));
     const int key = p.rows_in_flight * 10 + p.chunks_per_lane;
     switch (key) {

@@ -24,6 +24,7 @@ struct GatherArgs {
     const int32_t *slot;
     const char *cache;
     int high_priority;       // nonzero: the kernel raises its wavefronts' issue priority
+    int xcd_remap;           // nonzero: contiguous row ranges per XCD (grid is a multiple of 8)
 };
 
 // Resolved kernel parameters (every field concrete, see ud_tuning).
