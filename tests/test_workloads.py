@@ -45,3 +45,42 @@ def test_uniform_indices_cover_the_range():
         assert i.dtype == dt and i.min() == 0 and i.max() == 999
         counts = np.bincount(i, minlength=1000)
         assert counts.min() > 50 and counts.max() < 160
+
+
+def test_power_law_graph_and_csr_sampler():
+    N = 100_000
+    offsets, ids = workloads.zipf_graph_csr(N, 50, 25, 0.6, 9)
+    assert offsets.dtype == np.int64 and ids.dtype == np.int64 and offsets[0] == 0
+    deg = np.diff(offsets)
+    assert deg.min() == 25 and abs(deg.mean() - 50) < 0.05 and deg.max() > 10_000       # floor, mean, heavy head
+    assert ids.min() >= 0 and ids.max() < N and ids.size == offsets[-1]
+    # degree follows popularity rank: the most popular node has the largest degree
+    hot = workloads.hottest_nodes(N, 100, 9)
+    assert len(set(hot.tolist())) == 100 and deg[hot[0]] == deg.max()
+    assert (np.diff(deg[hot]) <= 0).all()
+    # popular nodes are named more often as neighbours
+    counts = np.bincount(ids, minlength=N)
+    assert counts[hot[:10]].mean() > 50 * counts.mean()
+    a = workloads.sample_csr(offsets, ids, 64, (25, 10), 5, 0)
+    b = workloads.sample_csr(offsets, ids, 64, (25, 10), 5, 0)
+    c = workloads.sample_csr(offsets, ids, 64, (25, 10), 5, 1)
+    assert np.array_equal(a, b) and not np.array_equal(a[:64], c[:64])                 # deterministic per (seed, batch)
+    assert len(np.unique(a)) == a.size and a.size <= workloads.slot_bound(64, (25, 10))
+    assert a.min() >= 0 and a.max() < N and a.size > 5_000
+    # every ID after the seeds is a neighbour of an earlier ID (first-occurrence order, seeds first)
+    nbrs = set()
+    for v in a[:64]:
+        nbrs.update(ids[offsets[v]:offsets[v + 1]].tolist())
+    assert set(a[64:64 + 200].tolist()) <= nbrs | set(a[:64].tolist())
+
+
+def test_procedural_sampler():
+    N = 5_000_000
+    a = workloads.sample_procedural(N, 30, 0.8, 4, 128, (15, 10, 5), 44, 0)
+    b = workloads.sample_procedural(N, 30, 0.8, 4, 128, (15, 10, 5), 44, 0)
+    assert np.array_equal(a, b) and len(np.unique(a)) == a.size
+    assert a.min() >= 0 and a.max() < N and 20_000 < a.size <= workloads.slot_bound(128, (15, 10, 5))
+    # the skew shows: the hottest 1 % of nodes take far more than 1 % of the batch
+    hot = set(workloads.hottest_nodes(N, N // 100, 4).tolist())
+    share = sum(int(v in hot) for v in a.tolist()) / a.size
+    assert share > 0.10
