@@ -413,11 +413,18 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
         w2 = torch.randn(hidden, hidden, device=dev) * 0.05
         layers = 1
 
+        consumer = {"kind": "gemm"}
+        scratch = torch.empty((M, D), dtype=torch.float32, device=dev)
+
         def consume(x):
-            h = torch.relu(x @ w1)
-            for _ in range(layers):
-                h = torch.relu(h @ w2)
-            return h.sum()
+            if consumer["kind"] == "gemm":                      # dense layers: MFMA-bound, statically partitioned kernels
+                h = torch.relu(x @ w1)
+                for _ in range(layers):
+                    h = torch.relu(h @ w2)
+                return h.sum()
+            for _ in range(consumer["passes"]):                 # element-wise passes: HBM-bound, many small workgroups
+                torch.mul(x, 1.0001, out=scratch)
+            return scratch
 
         sg, sc = torch.cuda.Stream(), torch.cuda.Stream()
 
@@ -504,6 +511,20 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                               "compute_ms_while_overlapped": round(spans["compute"], 3),
                               "exposed_gather_ms": round(max(to - t_c, 0.0), 3),
                               "hidden_fraction_of_gather": round(1.0 - max(to - t_c, 0.0) / tg, 3)}
+        # the same pipeline with a bandwidth-bound, finely divided consumer of about the same length
+        consumer.update(kind="elementwise", passes=8)
+        t_e = timed(only_compute) / nb
+        consumer["passes"] = max(1, round(8 * t_c / t_e))
+        t_e = timed(only_compute) / nb
+        elementwise = {"compute_only_ms": round(t_e, 3), "passes": consumer["passes"]}
+        for name, tun in (("auto_512wg", None), ("128wg", ud.ud_tuning(0, 0, 0, 128, 0)), ("64wg", ud.ud_tuning(0, 0, 0, 64, 0))):
+            tg = timed(only_gather(tun)) / nb
+            to = timed(overlapped(tun)) / nb
+            elementwise[name] = {"gather_only_ms": round(tg, 3), "overlapped_ms": round(to, 3),
+                                 "gather_ms_while_overlapped": round(spans["gather"], 3),
+                                 "compute_ms_while_overlapped": round(spans["compute"], 3),
+                                 "hidden_fraction_of_gather": round(1.0 - max(to - t_e, 0.0) / tg, 3)}
+        consumer["kind"] = "gemm"
         ud.ud_gather_status(sg.cuda_stream)
         ok = spot_check(table, N, D, oracle.F32, np.ascontiguousarray(ids_np[nb - 1][:M]), bufs[(nb - 1) & 1].view(-1))
         best = min(variants.values(), key=lambda v: v["overlapped_ms"])
@@ -511,7 +532,8 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                       {"workload": f"overlap: zero-copy gather of batch b+1 ({M} rows x 1024 B from a 16,000,000-row host table) "
                                    f"on one stream while {layers + 1} dense fp32 layers (hidden {hidden}) consume batch b on another; "
                                    "value = gathered bytes / per-batch time of the overlapped pipeline"},
-                      compute_only_ms=round(t_c, 3), variants=variants, parity_spot_check=ok)
+                      compute_only_ms=round(t_c, 3), variants=variants, elementwise_consumer=elementwise,
+                      parity_spot_check=ok)
 
     if wl == "fp16":
         N, D, M = 10_000_000, 602, 2_000_000

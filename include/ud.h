@@ -155,7 +155,10 @@ ud_status ud_gather_cached(const ud_cache *c, ud_dtype dtype, const void *idx, u
  *   chunks_per_lane  1..4: 16-byte chunks of one row each lane keeps in flight
  *   rows_in_flight   1, 2 or 4: rows each lane group loads before storing any
  *                    (rows_in_flight x chunks_per_lane <= 8; 4 x 2 is not built)
- *   max_blocks       cap on workgroups (grid-stride beyond it)
+ *   max_blocks       cap on workgroups (grid-stride beyond it).  A gather that should run beside another
+ *                    stream's kernels needs a small grid: with 256 or more workgroups nothing else is
+ *                    scheduled until it ends, with 64..128 it overlaps (rows of 1 KiB or more then still
+ *                    reach the full link rate; shorter rows want rows_in_flight > 1 as well)
  *   flags            UD_TUNE_* bits
  */
 typedef struct {
