@@ -517,7 +517,8 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
         consumer["passes"] = max(1, round(8 * t_c / t_e))
         t_e = timed(only_compute) / nb
         elementwise = {"compute_only_ms": round(t_e, 3), "passes": consumer["passes"]}
-        for name, tun in (("auto_512wg", None), ("128wg", ud.ud_tuning(0, 0, 0, 128, 0)), ("64wg", ud.ud_tuning(0, 0, 0, 64, 0))):
+        for name, tun in (("auto_512wg", None), ("128wg", ud.ud_tuning(0, 0, 0, 128, 0)), ("64wg", ud.ud_tuning(0, 0, 0, 64, 0)),
+                          ("share_gpu_flag", ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU))):
             tg = timed(only_gather(tun)) / nb
             to = timed(overlapped(tun)) / nb
             elementwise[name] = {"gather_only_ms": round(tg, 3), "overlapped_ms": round(to, 3),

@@ -181,6 +181,10 @@ enum {
                                    the paper (its alignment fix), for comparison */
     UD_TUNE_XCD_REMAP = 64u,    /* renumber workgroups so that each of the 8 XCDs (each with its own L2) serves one
                                    contiguous range of output rows */
+    UD_TUNE_SHARE_GPU = 128u,   /* launch shape for a gather that runs beside another stream's kernels: a grid of
+                                   64 workgroups for rows of 1 KiB or more, 128 below (unless max_blocks is given),
+                                   and enough rows in flight per lane group to keep about 1 KiB per wavefront on
+                                   the link; 94-100% of the stand-alone rate */
     UD_TUNE_ELEMENTWISE = 4u    /* one lane per element, rows straddling wavefronts: the layout of
                                    the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
                                    the comparison point and as the fallback for odd alignments */

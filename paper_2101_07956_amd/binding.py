@@ -22,7 +22,7 @@ UD_F32, UD_F16, UD_F16_TO_F32 = 0, 1, 2
 UD_I64, UD_I32 = 0, 1
 UD_TABLE_COHERENT, UD_TABLE_NONCOHERENT = 0, 1
 UD_TUNE_NT_LOAD, UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE, UD_TUNE_WAVE_PRIORITY, UD_TUNE_BIG_BLOCKS = 1, 2, 4, 8, 16
-UD_TUNE_CIRCULAR_SHIFT, UD_TUNE_XCD_REMAP = 32, 64
+UD_TUNE_CIRCULAR_SHIFT, UD_TUNE_XCD_REMAP, UD_TUNE_SHARE_GPU = 32, 64, 128
 
 #: every symbol include/ud.h declares
 EXPORTS = (

@@ -291,7 +291,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
     ud::Plan plan = auto_plan(table, D, dtype);
     if (tuning) {
         if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_WAVE_PRIORITY | UD_TUNE_BIG_BLOCKS |
-                              UD_TUNE_CIRCULAR_SHIFT | UD_TUNE_XCD_REMAP))
+                              UD_TUNE_CIRCULAR_SHIFT | UD_TUNE_XCD_REMAP | UD_TUNE_SHARE_GPU))
             return UD_ERR_INVALID_ARG;
         if ((tuning->flags & UD_TUNE_CIRCULAR_SHIFT) && !(tuning->flags & UD_TUNE_ELEMENTWISE))
             return UD_ERR_INVALID_ARG;
@@ -316,6 +316,19 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
             plan.rows_in_flight = 1;
         if (tuning->max_blocks)
             plan.max_blocks = tuning->max_blocks;
+        if (tuning->flags & UD_TUNE_SHARE_GPU) {
+            // few wavefronts, each with about 1 KiB on the link: 64 workgroups x 4 wavefronts cover the
+            // link's round trip for rows of 1 KiB and more (measured: 99-100% of the stand-alone rate),
+            // 128 workgroups are needed below that (94-98%); either leaves the compute units free
+            // for the other stream's kernels, 256 or more do not
+            const int64_t rb = D * elem_bytes(dtype);
+            if (!tuning->max_blocks)
+                plan.max_blocks = rb >= 1024 ? 64 : 128;
+            if (!tuning->rows_in_flight && !tuning->chunks_per_lane && plan.chunks_per_lane == 1) {
+                const int64_t per_pass = rb * (64 / plan.lanes_per_row);     // bytes one wavefront instruction fetches
+                plan.rows_in_flight = per_pass >= 1024 ? 1 : per_pass >= 512 ? 2 : 4;
+            }
+        }
         if (plan.rows_in_flight * plan.chunks_per_lane > 8 || (plan.rows_in_flight == 4 && plan.chunks_per_lane == 2))
             return UD_ERR_UNSUPPORTED;
     }

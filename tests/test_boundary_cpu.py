@@ -83,7 +83,7 @@ def test_tuning_fields_are_range_checked(ud):
     assert _gather(ud, tuning=T(0, 5, 0, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 3, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, -1, 0)) == inv
-    assert _gather(ud, tuning=T(0, 0, 0, 0, 128)) == inv
+    assert _gather(ud, tuning=T(0, 0, 0, 0, 256)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, 0, 32)) == inv       # circular shift needs the one-lane-per-element kernel
     assert _gather(ud, tuning=T(0, 0, 8, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 4, 4, 0, 0)) == ud.UD_ERR_UNSUPPORTED   # no such instantiation

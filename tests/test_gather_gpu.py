@@ -159,6 +159,16 @@ def test_circular_shift_kernel_widths(ud, D):
     t.free()
 
 
+@pytest.mark.parametrize("D", [16, 64, 100, 256, 602])
+def test_share_gpu_launch_shape(ud, D):
+    N, M = 20_000, 30_011
+    t = make_table(ud, N, D, ud.UD_F32, 30 + D)
+    idx = workloads.indices_uniform(31, M, N)
+    got = run_gather(ud, t, idx, ud.UD_F32, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU))
+    assert np.array_equal(got, oracle_bits(t.numpy(), idx, oracle.F32)), D
+    t.free()
+
+
 def test_index_patterns(ud):
     N, D = 4099, 100
     t = make_table(ud, N, D, ud.UD_F32, 12)
