@@ -524,3 +524,31 @@ def test_device_resident_fp16_table(ud, D):
         assert np.array_equal(run_gather(ud, dev, idx, dtype), oracle_bits(host.numpy(), idx, dtype)), (D, dtype)
     dev.free()
     host.free()
+
+
+def test_torch_convenience_wrapper(ud):
+    # table.py only marshals: pointers from torch tensors, output allocation, stream
+    N, D, M = 5000, 100, 3001
+    t = make_table(ud, N, D, ud.UD_F32, 80)
+    idx_np = workloads.indices_uniform(81, M, N)
+    idx = torch.from_numpy(idx_np).cuda()
+    out = ud.gather(t, idx, check=True)
+    assert out.shape == (M, D) and out.dtype == torch.float32 and out.is_cuda
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), oracle_bits(t.numpy(), idx_np, oracle.F32))
+    pre = torch.empty((M, D), dtype=torch.float32, device="cuda")
+    assert ud.gather(t, idx.to(torch.int32), out=pre, check=True) is pre
+    assert torch.equal(pre, out)
+    bad = idx.clone()
+    bad[7] = N
+    with pytest.raises(ud.UdIndexError):
+        ud.gather(t, bad, check=True)
+    h = make_table(ud, N, D, ud.UD_F16, 82)
+    o16 = ud.gather(h, idx, check=True)
+    o32 = ud.gather(h, idx, widen=True, check=True)
+    assert o16.dtype == torch.float16 and o32.dtype == torch.float32
+    assert np.array_equal(o32.cpu().numpy().view(np.uint32), oracle_bits(h.numpy(), idx_np, oracle.F16_TO_F32))
+    assert torch.equal(o16.float(), o32)
+    with pytest.raises(ValueError):
+        t.to_device().numpy()
+    h.free()
+    t.free()
