@@ -56,6 +56,12 @@ def _load():
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
             ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
         ]
+        lib.oracle_gather_pitched.restype = ctypes.c_int
+        lib.oracle_gather_pitched.argtypes = [
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+            ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
+        ]
         lib.oracle_scatter.restype = ctypes.c_int
         lib.oracle_scatter.argtypes = [
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
@@ -76,13 +82,20 @@ def _load():
 _TABLE_NP = {F32: (np.uint32, np.uint32), F16: (np.uint16, np.uint16), F16_TO_F32: (np.uint16, np.uint32)}
 
 
-def gather_raw(table_ptr: int, N: int, D: int, dtype: int, idx: np.ndarray, out: np.ndarray) -> None:
-    """Oracle gather from a raw host address (for tables that live in pinned memory)."""
+def gather_raw(table_ptr: int, N: int, D: int, dtype: int, idx: np.ndarray, out: np.ndarray,
+               pitch: int | None = None) -> None:
+    """Oracle gather from a raw host address (for tables that live in pinned memory).
+
+    ``pitch`` is the distance between rows in elements (default ``D``: a dense table)."""
     itype = {np.dtype(np.int64): I64, np.dtype(np.int32): I32}[idx.dtype]
     assert idx.flags.c_contiguous and out.flags.c_contiguous
     bad = ctypes.c_int64(-1)
-    rc = _load().oracle_gather(table_ptr, N, D, dtype, idx.ctypes.data, itype, idx.size,
-                               out.ctypes.data, ctypes.byref(bad))
+    if pitch is None:
+        rc = _load().oracle_gather(table_ptr, N, D, dtype, idx.ctypes.data, itype, idx.size,
+                                   out.ctypes.data, ctypes.byref(bad))
+    else:
+        rc = _load().oracle_gather_pitched(table_ptr, N, D, pitch, dtype, idx.ctypes.data, itype, idx.size,
+                                           out.ctypes.data, ctypes.byref(bad))
     if rc == ERR_INDEX:
         raise OracleIndexError(bad.value)
     if rc != OK:

@@ -95,13 +95,30 @@ static int64_t read_index(const void *idx, int itype, int64_t i)
  * the first one outside [0, N), *bad_pos = i, ORACLE_ERR_INDEX is returned and
  * out is untouched.  Otherwise *bad_pos = -1.
  */
+int oracle_gather_pitched(const void *table, int64_t N, int64_t D, int64_t pitch, int dtype,
+                          const void *idx, int itype, int64_t M,
+                          void *out, int64_t *bad_pos);
+
 int oracle_gather(const void *table, int64_t N, int64_t D, int dtype,
                   const void *idx, int itype, int64_t M,
                   void *out, int64_t *bad_pos)
 {
+    return oracle_gather_pitched(table, N, D, D, dtype, idx, itype, M, out, bad_pos);
+}
+
+/*
+ * The same gather from a table whose rows are `pitch` elements apart
+ * (pitch >= D; elements D..pitch-1 of every row are padding and never read):
+ *     out[i*D + j] = conv(table[idx[i]*pitch + j]).
+ * The output stays dense.  pitch == D is the paper's plain 2-D array.
+ */
+int oracle_gather_pitched(const void *table, int64_t N, int64_t D, int64_t pitch, int dtype,
+                          const void *idx, int itype, int64_t M,
+                          void *out, int64_t *bad_pos)
+{
     if (bad_pos)
         *bad_pos = -1;
-    if (N < 1 || D < 1 || M < 0)
+    if (N < 1 || D < 1 || M < 0 || pitch < D)
         return ORACLE_ERR_INVALID_ARG;
     if (dtype != ORACLE_F32 && dtype != ORACLE_F16 && dtype != ORACLE_F16_TO_F32)
         return ORACLE_ERR_INVALID_ARG;
@@ -124,7 +141,7 @@ int oracle_gather(const void *table, int64_t N, int64_t D, int dtype,
     for (int64_t i = 0; i < M; ++i) {
         const int64_t r = read_index(idx, itype, i);
         for (int64_t j = 0; j < D; ++j) {
-            const int64_t src = r * D + j;
+            const int64_t src = r * pitch + j;
             const int64_t dst = i * D + j;
             if (dtype == ORACLE_F32)
                 ((uint32_t *)out)[dst] = ((const uint32_t *)table)[src];

@@ -153,3 +153,31 @@ def test_invalid_arguments():
             oracle.gather_raw(table.ctypes.data, N, D, oracle.F32, idx, out)
     with pytest.raises(ValueError):
         oracle.gather_raw(table.ctypes.data, 4, 4, 7, idx, out)
+
+
+@pytest.mark.parametrize("D,pitch", [(1, 1), (3, 8), (100, 128), (602, 608), (602, 602), (5, 37)])
+def test_pitched_table_matches_numpy_on_the_padded_array(D, pitch):
+    # rows `pitch` elements apart, only the first D of each are data
+    N, M = 501, 777
+    padded = workloads.uniform_f32(21, N, pitch)
+    idx = workloads.indices_uniform(22, M, N)
+    out = np.full((M, D), 0xA5A5A5A5, dtype=np.uint32)
+    oracle.gather_raw(padded.ctypes.data, N, D, oracle.F32, idx, out, pitch=pitch)
+    assert np.array_equal(out, np.take(padded, idx, axis=0)[:, :D].view(np.uint32))
+
+
+def test_pitched_tag_table_closed_form_and_padding_is_never_read():
+    N, D, pitch, M = 300, 11, 16, 400
+    table = workloads.tag_table(N, pitch)                       # element (r, c) of the padded array holds r*pitch + c
+    table[:, D:] = 0xFFFFFFFF                                    # poison the padding
+    idx = workloads.indices_uniform(23, M, N, np.int32)
+    out = np.empty((M, D), dtype=np.uint32)
+    oracle.gather_raw(table.ctypes.data, N, D, oracle.F32, idx, out, pitch=pitch)
+    assert np.array_equal(out.astype(np.int64), idx.astype(np.int64)[:, None] * pitch + np.arange(D)[None, :])
+
+
+def test_pitch_smaller_than_width_is_invalid():
+    table = workloads.uniform_f32(24, 4, 8)
+    with pytest.raises(ValueError):
+        oracle.gather_raw(table.ctypes.data, 4, 8, oracle.F32, np.zeros(1, dtype=np.int64),
+                          np.empty((1, 8), dtype=np.uint32), pitch=7)
