@@ -536,6 +536,60 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                       compute_only_ms=round(t_c, 3), variants=variants, elementwise_consumer=elementwise,
                       parity_spot_check=ok)
 
+    if wl == "padded":
+        # the same gathers from tables whose row pitch is rounded up to 128 bytes (UD_TABLE_PAD_ROWS):
+        # no row shares a memory line with its neighbours, so nothing but the row's own lines is fetched
+        N, M = N_ROWS, M_ROWS
+        stream = torch.cuda.current_stream().cuda_stream
+        reps = min(K, 10)
+        cases, ok = {}, True
+        tot_b = tot_ms = 0.0
+        for name, elem, dtype, odtype, D in (("f32_D100", ud.UD_F32, ud.UD_F32, oracle.F32, 100),
+                                             ("f32_D602", ud.UD_F32, ud.UD_F32, oracle.F32, 602),
+                                             ("f16_to_f32_D602", ud.UD_F16, ud.UD_F16_TO_F32, oracle.F16_TO_F32, 602)):
+            esz = 4 if elem == ud.UD_F32 else 2
+            ids_np = [workloads.indices_uniform(workloads.IDX_STREAM + k, M, N) for k in range(reps + W)]
+            ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
+            out = torch.empty(M * D, dtype=torch.float32, device=dev)
+            r = {}
+            for kind, flags in (("dense", 0), ("padded", ud.UD_TABLE_PAD_ROWS)):
+                t = ud.Table(N, D, elem, flags)
+                if elem == ud.UD_F32:
+                    workloads.fill_uniform_f32(t.host_ptr, 9, N * t.pitch)
+                else:
+                    workloads.fill_normal_f16(t.host_ptr, 9, N * t.pitch)
+                ev = []
+                for k, ids in enumerate(ids_dev):
+                    if k >= W:
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                    ud.ud_gather_pitched(t.device_ptr, N, D, t.pitch, dtype, ids.data_ptr(), ud.UD_I64, M, out.data_ptr(), stream)
+                    if k >= W:
+                        e1.record()
+                        ev.append((e0, e1))
+                torch.cuda.synchronize()
+                ud.ud_gather_status(stream)
+                st = _stats([a.elapsed_time(b) for a, b in ev])
+                samp = np.sort(np.random.default_rng(0).choice(M, 2048, replace=False))
+                got = out.view(M, D)[torch.from_numpy(samp).to(dev)].cpu().numpy()
+                want = np.empty((samp.size, D), dtype=np.uint32)
+                oracle.gather_raw(t.host_ptr, N, D, odtype, np.ascontiguousarray(ids_np[-1][samp]), want, pitch=t.pitch)
+                ok = ok and bool(np.array_equal(got.view(np.uint32), want))
+                useful = M * D * esz
+                r[kind] = {"pitch_bytes": t.pitch * esz, "ms": st["median_ms"], "GBps": round(useful / st["median_ms"] / 1e6, 2),
+                           "frac_of_h2d_peak": round(useful / st["median_ms"] / 1e6 / h2d_peak, 4),
+                           "table_GB": round(t.nbytes / 1e9, 2)}
+                if kind == "padded":
+                    tot_b += useful
+                    tot_ms += st["median_ms"]
+                t.free()
+            r["speedup"] = round(r["dense"]["ms"] / r["padded"]["ms"], 3)
+            cases[name] = r
+        return finish(tot_b / tot_ms / 1e6, tot_ms, "f32",
+                      {"workload": "padded rows: 1,000,000 int64 IDs from 4,000,000-row host-pinned tables with the row pitch "
+                                   "rounded up to 128 bytes, against the dense layout; value = useful bytes / time, padded tables"},
+                      cases=cases, parity_spot_check=ok)
+
     if wl == "fp16":
         N, D, M = 10_000_000, 602, 2_000_000
         table = ud.Table(N, D, ud.UD_F16)
@@ -641,7 +695,7 @@ def main() -> int:
     ap.add_argument("--threads", type=int, default=0, help="host threads of the CPU-centric baseline (0 = all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host baselines (for profiling runs)")
     ap.add_argument("--workload", default="sweep",
-                    choices=("sweep", "single", "graphsage", "large", "fp16", "align", "grid", "hybrid", "scatter", "overlap"),
+                    choices=("sweep", "single", "graphsage", "large", "fp16", "align", "grid", "hybrid", "scatter", "overlap", "padded"),
                     help="sweep (default, the headline microbenchmark) or one of the other configurations / "
                          "the paper's alignment and size experiments")
     args = ap.parse_args()

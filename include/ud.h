@@ -53,8 +53,13 @@ typedef enum { UD_I64 = 0, UD_I32 = 1 } ud_itype;
 /* flags for ud_alloc_table */
 enum {
     UD_TABLE_COHERENT = 0,     /* fine-grained (host-coherent) pinned memory: the default */
-    UD_TABLE_NONCOHERENT = 1   /* coarse-grained pinned memory: GPU caches may keep lines, so CPU
+    UD_TABLE_NONCOHERENT = 1,  /* coarse-grained pinned memory: GPU caches may keep lines, so CPU
                                   writes made while a kernel runs may not be seen by it */
+    UD_TABLE_PAD_ROWS = 2      /* row pitch rounded up to a multiple of 128 bytes, so that every row starts on
+                                  a memory line of its own.  The GPU fetches host memory in whole 128-byte
+                                  lines; rows of a dense table whose size is no multiple of 128 share their
+                                  first and last line with their neighbours and fetch up to 127 bytes more
+                                  than they hold (2408-byte rows: 5% more).  Read the pitch with ud_table_pitch */
 };
 
 typedef struct ud_table ud_table; /* opaque handle, owned by the library */
@@ -87,6 +92,9 @@ ud_status ud_table_host_ptr(const ud_table *t, void **p);
 ud_status ud_table_device_ptr(const ud_table *t, const void **p);
 /* Shape and element type as given at allocation. */
 ud_status ud_table_shape(const ud_table *t, int64_t *N, int64_t *D, ud_dtype *elem);
+/* Elements between the starts of consecutive rows: D, or more for UD_TABLE_PAD_ROWS.
+ * Element (r, c) of the table is at index r * pitch + c from the row-0 pointer. */
+ud_status ud_table_pitch(const ud_table *t, int64_t *pitch);
 /* Releases the handle and its memory.  NULL is a no-op.  No gather that reads
  * the table may still be in flight. */
 ud_status ud_free_table(ud_table *t);
@@ -122,6 +130,17 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
                     void *out, void *stream);
 
 /*
+ * ud_gather from a table whose rows are `pitch` elements apart (pitch >= D; the
+ * elements D .. pitch-1 of each row are padding and are never read): out[i, j] =
+ * conv(table[idx[i] * pitch + j]).  The output stays dense (row stride D).  This
+ * is the form to use with UD_TABLE_PAD_ROWS tables.  Everything else as ud_gather;
+ * extra error: UD_ERR_INVALID_ARG for pitch < D.
+ */
+ud_status ud_gather_pitched(const void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
+                            const void *idx, ud_itype itype, int64_t M,
+                            void *out, void *stream);
+
+/*
  * Hot-row cache (hybrid placement).  The paper's placement discussion (Section
  * 4.3) notes that data which is reused is better held in GPU memory than
  * re-read over the host link; node IDs of power-law graphs are heavily skewed,
@@ -131,7 +150,7 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
  * cached and over the host link otherwise, in one kernel.  Results are
  * identical to ud_gather on the same table.
  *
- *   table     a host table (ud_alloc_table); must outlive the cache and must
+ *   table     a host table (ud_alloc_table, dense or padded); must outlive the cache and must
  *             not be written while the cache exists (cached copies would go stale)
  *   hot_rows  host pointer to n_hot row IDs in [0, N); duplicates are tolerated
  *   n_hot     1 .. min(N, 2^31 - 1)

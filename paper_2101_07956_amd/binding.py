@@ -20,14 +20,14 @@ LIB_PATH = os.path.join(_PKG, "libud.so")
 UD_OK, UD_ERR_INVALID_ARG, UD_ERR_UNSUPPORTED, UD_ERR_OOM, UD_ERR_INDEX_OUT_OF_RANGE, UD_ERR_HIP = range(6)
 UD_F32, UD_F16, UD_F16_TO_F32 = 0, 1, 2
 UD_I64, UD_I32 = 0, 1
-UD_TABLE_COHERENT, UD_TABLE_NONCOHERENT = 0, 1
+UD_TABLE_COHERENT, UD_TABLE_NONCOHERENT, UD_TABLE_PAD_ROWS = 0, 1, 2
 UD_TUNE_NT_LOAD, UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE, UD_TUNE_WAVE_PRIORITY, UD_TUNE_BIG_BLOCKS = 1, 2, 4, 8, 16
 UD_TUNE_CIRCULAR_SHIFT, UD_TUNE_XCD_REMAP, UD_TUNE_SHARE_GPU = 32, 64, 128
 
 #: every symbol include/ud.h declares
 EXPORTS = (
     "ud_alloc_table", "ud_table_to_device", "ud_table_host_ptr", "ud_table_device_ptr",
-    "ud_table_shape", "ud_free_table", "ud_gather", "ud_gather_tuned", "ud_gather_plan",
+    "ud_table_shape", "ud_table_pitch", "ud_free_table", "ud_gather", "ud_gather_pitched", "ud_gather_tuned", "ud_gather_plan",
     "ud_gather_status", "ud_cache_create", "ud_cache_free", "ud_gather_cached",
     "ud_scatter", "ud_scatter_tuned", "ud_status_str", "ud_last_hip_error",
 )
@@ -72,6 +72,8 @@ _lib.ud_table_to_device.argtypes = [_vp, _i64, _i64, ctypes.POINTER(_vp)]
 _lib.ud_table_host_ptr.argtypes = [_vp, ctypes.POINTER(_vp)]
 _lib.ud_table_device_ptr.argtypes = [_vp, ctypes.POINTER(_vp)]
 _lib.ud_table_shape.argtypes = [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_int)]
+_lib.ud_table_pitch.argtypes = [_vp, ctypes.POINTER(_i64)]
+_lib.ud_gather_pitched.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_free_table.argtypes = [_vp]
 _lib.ud_gather.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_gather_tuned.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp, ctypes.POINTER(ud_tuning)]
@@ -133,6 +135,18 @@ def ud_table_shape(t: int) -> tuple[int, int, int]:
     N, D, e = _i64(), _i64(), _int()
     _check(_lib.ud_table_shape(t, ctypes.byref(N), ctypes.byref(D), ctypes.byref(e)), "ud_table_shape")
     return N.value, D.value, e.value
+
+
+def ud_table_pitch(t: int) -> int:
+    p = _i64()
+    _check(_lib.ud_table_pitch(t, ctypes.byref(p)), "ud_table_pitch")
+    return p.value
+
+
+def ud_gather_pitched(table: int, N: int, D: int, pitch: int, dtype: int, idx: int, itype: int, M: int, out: int,
+                      stream: int | None = None) -> None:
+    """``ud_gather`` from a table whose rows are ``pitch`` elements apart."""
+    _check(_lib.ud_gather_pitched(table, N, D, pitch, dtype, idx, itype, M, out, stream), "ud_gather_pitched")
 
 
 def ud_free_table(t: int | None) -> None:

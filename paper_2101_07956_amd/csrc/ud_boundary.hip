@@ -17,6 +17,7 @@ struct ud_table {
     void *host;      // CPU address of row 0, nullptr when device-resident
     void *dev;       // GPU address of row 0
     int64_t N, D;
+    int64_t pitch;   // elements between rows, >= D
     ud_dtype elem;
     bool device_resident;
 };
@@ -24,6 +25,7 @@ struct ud_table {
 struct ud_cache {
     const void *table; // GPU address of the host table's row 0
     int64_t N, D;
+    int64_t pitch;     // the host table's row pitch in elements
     ud_dtype elem;
     void *rows;        // HBM copy of the hot rows, slot-major
     int32_t *slot;     // HBM, N entries: slot of each table row in `rows`, or -1
@@ -92,11 +94,11 @@ int next_pow2(int64_t x)
 
 // Largest number of 16-byte chunks any row can overlap, given the base address
 // and the row pitch: the row start offsets modulo 16 cycle with period <= 16.
-int64_t max_chunks_per_row(uintptr_t base, int64_t row_bytes)
+int64_t max_chunks_per_row(uintptr_t base, int64_t row_bytes, int64_t pitch_bytes)
 {
     int64_t worst_head = 0;
     for (int k = 0; k < 16; ++k) {
-        const int64_t head = static_cast<int64_t>((base + static_cast<uintptr_t>(k) * static_cast<uintptr_t>(row_bytes)) & 15u);
+        const int64_t head = static_cast<int64_t>((base + static_cast<uintptr_t>(k) * static_cast<uintptr_t>(pitch_bytes)) & 15u);
         if (head > worst_head)
             worst_head = head;
     }
@@ -136,10 +138,10 @@ bool table_is_in_hbm(const void *table)
 //    row; below that, one wavefront batch per workgroup slot is best.
 //  * HBM table (bandwidth-bound): no idle lanes (lanes per row = chunks per row
 //    rounded up to a power of two), two rows in flight, streaming stores.
-ud::Plan auto_plan(const void *table, int64_t D, ud_dtype dtype)
+ud::Plan auto_plan(const void *table, int64_t D, int64_t pitch, ud_dtype dtype)
 {
     const int64_t row_bytes = D * elem_bytes(dtype);
-    const int64_t nch = max_chunks_per_row(reinterpret_cast<uintptr_t>(table), row_bytes);
+    const int64_t nch = max_chunks_per_row(reinterpret_cast<uintptr_t>(table), row_bytes, pitch * elem_bytes(dtype));
     const bool hbm = table_is_in_hbm(table);
     ud::Plan p{};
     p.flags = hbm ? UD_TUNE_NT_STORE : 0u;
@@ -167,10 +169,18 @@ extern "C" {
 
 ud_status ud_alloc_table(int64_t N, int64_t D, ud_dtype elem, unsigned flags, ud_table **t)
 {
-    if (!t || N < 1 || D < 1 || (elem != UD_F32 && elem != UD_F16) || (flags & ~1u))
+    if (!t || N < 1 || D < 1 || (elem != UD_F32 && elem != UD_F16) || (flags & ~3u))
         return UD_ERR_INVALID_ARG;
+    int64_t pitch = D;
+    if (flags & UD_TABLE_PAD_ROWS) {
+        // rows start on 128-byte lines: no row shares a line with its neighbours
+        const int64_t per_line = 128 / elem_bytes(elem);
+        if (D > INT64_MAX - per_line)
+            return UD_ERR_INVALID_ARG;
+        pitch = (D + per_line - 1) / per_line * per_line;
+    }
     int64_t bytes;
-    if (mul3_overflows(N, D, elem_bytes(elem), &bytes))
+    if (mul3_overflows(N, pitch, elem_bytes(elem), &bytes))
         return UD_ERR_INVALID_ARG;
     const unsigned hip_flags =
         hipHostMallocMapped | ((flags & UD_TABLE_NONCOHERENT) ? hipHostMallocNonCoherent : hipHostMallocCoherent);
@@ -184,7 +194,7 @@ ud_status ud_alloc_table(int64_t N, int64_t D, ud_dtype elem, unsigned flags, ud
         (void)hipHostFree(host);
         return hip_fail(e, "hipHostGetDevicePointer");
     }
-    ud_table *h = new (std::nothrow) ud_table{host, dev, N, D, elem, false};
+    ud_table *h = new (std::nothrow) ud_table{host, dev, N, D, pitch, elem, false};
     if (!h) {
         (void)hipHostFree(host);
         return UD_ERR_OOM;
@@ -197,7 +207,7 @@ ud_status ud_table_to_device(const ud_table *src, int64_t row0, int64_t n, ud_ta
 {
     if (!src || !t || src->device_resident || row0 < 0 || n < 1 || row0 > src->N - n)
         return UD_ERR_INVALID_ARG;
-    const int64_t row_bytes = src->D * elem_bytes(src->elem);
+    const int64_t row_bytes = src->pitch * elem_bytes(src->elem);   // the copy keeps the pitch
     const size_t bytes = static_cast<size_t>(n) * static_cast<size_t>(row_bytes);
     void *dev = nullptr;
     hipError_t e = hipMalloc(&dev, bytes);
@@ -208,7 +218,7 @@ ud_status ud_table_to_device(const ud_table *src, int64_t row0, int64_t n, ud_ta
         (void)hipFree(dev);
         return hip_fail(e, "hipMemcpy(table)");
     }
-    ud_table *h = new (std::nothrow) ud_table{nullptr, dev, n, src->D, src->elem, true};
+    ud_table *h = new (std::nothrow) ud_table{nullptr, dev, n, src->D, src->pitch, src->elem, true};
     if (!h) {
         (void)hipFree(dev);
         return UD_ERR_OOM;
@@ -246,6 +256,14 @@ ud_status ud_table_shape(const ud_table *t, int64_t *N, int64_t *D, ud_dtype *el
     return UD_OK;
 }
 
+ud_status ud_table_pitch(const ud_table *t, int64_t *pitch)
+{
+    if (!t || !pitch)
+        return UD_ERR_INVALID_ARG;
+    *pitch = t->pitch;
+    return UD_OK;
+}
+
 ud_status ud_free_table(ud_table *t)
 {
     if (!t)
@@ -262,7 +280,7 @@ ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning
     int64_t row_bytes;
     if (__builtin_mul_overflow(D, static_cast<int64_t>(elem_bytes(dtype)), &row_bytes) || row_bytes > INT64_MAX - 64)
         return UD_ERR_INVALID_ARG;
-    const ud::Plan p = auto_plan(table, D, dtype);
+    const ud::Plan p = auto_plan(table, D, D, dtype);
     plan->lanes_per_row = p.lanes_per_row;
     plan->chunks_per_lane = p.chunks_per_lane;
     plan->rows_in_flight = p.rows_in_flight;
@@ -271,24 +289,24 @@ ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning
     return UD_OK;
 }
 
-static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
                              const void *idx, ud_itype itype, int64_t M,
                              void *out, void *stream, const ud_tuning *tuning,
                              const int32_t *slot, const char *cache)
 {
-    if (N < 1 || D < 1 || M < 0)
+    if (N < 1 || D < 1 || M < 0 || pitch < D)
         return UD_ERR_INVALID_ARG;
     if (dtype != UD_F32 && dtype != UD_F16 && dtype != UD_F16_TO_F32)
         return UD_ERR_INVALID_ARG;
     if (itype != UD_I64 && itype != UD_I32)
         return UD_ERR_INVALID_ARG;
     int64_t table_bytes, out_bytes;
-    if (mul3_overflows(N, D, elem_bytes(dtype), &table_bytes) || mul3_overflows(M, D, out_elem_bytes(dtype), &out_bytes))
+    if (mul3_overflows(N, pitch, elem_bytes(dtype), &table_bytes) || mul3_overflows(M, D, out_elem_bytes(dtype), &out_bytes))
         return UD_ERR_INVALID_ARG;
     if (table_bytes > INT64_MAX - 64)
         return UD_ERR_INVALID_ARG;
 
-    ud::Plan plan = auto_plan(table, D, dtype);
+    ud::Plan plan = auto_plan(table, D, pitch, dtype);
     if (tuning) {
         if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_WAVE_PRIORITY | UD_TUNE_BIG_BLOCKS |
                               UD_TUNE_CIRCULAR_SHIFT | UD_TUNE_XCD_REMAP | UD_TUNE_SHARE_GPU))
@@ -345,6 +363,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, ud_dtype d
     a.table = static_cast<const char *>(table);
     a.N = N;
     a.D = D;
+    a.pitch_bytes = pitch * elem_bytes(dtype);
     a.idx = idx;
     a.itype = itype;
     a.M = M;
@@ -378,14 +397,21 @@ ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtyp
                           const void *idx, ud_itype itype, int64_t M,
                           void *out, void *stream, const ud_tuning *tuning)
 {
-    return gather_impl(table, N, D, dtype, idx, itype, M, out, stream, tuning, nullptr, nullptr);
+    return gather_impl(table, N, D, D, dtype, idx, itype, M, out, stream, tuning, nullptr, nullptr);
+}
+
+ud_status ud_gather_pitched(const void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
+                            const void *idx, ud_itype itype, int64_t M,
+                            void *out, void *stream)
+{
+    return gather_impl(table, N, D, pitch, dtype, idx, itype, M, out, stream, nullptr, nullptr, nullptr);
 }
 
 ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
                     const void *idx, ud_itype itype, int64_t M,
                     void *out, void *stream)
 {
-    return gather_impl(table, N, D, dtype, idx, itype, M, out, stream, nullptr, nullptr, nullptr);
+    return gather_impl(table, N, D, D, dtype, idx, itype, M, out, stream, nullptr, nullptr, nullptr);
 }
 
 ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
@@ -403,7 +429,7 @@ ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
         return UD_ERR_INVALID_ARG;
     if (table_bytes > INT64_MAX - 64)
         return UD_ERR_INVALID_ARG;
-    ud::Plan plan = auto_plan(table, D, dtype);
+    ud::Plan plan = auto_plan(table, D, D, dtype);
     plan.flags = 0;
     if (tuning) {
         if (tuning->flags)
@@ -440,6 +466,7 @@ ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
     a.itype = itype;
     a.M = M;
     a.out = const_cast<void *>(src);
+    a.pitch_bytes = D * elem_bytes(dtype);
     const ud_status es = error_word(&a.err);
     if (es != UD_OK)
         return es;
@@ -472,6 +499,7 @@ ud_status ud_cache_create(const ud_table *table, const int64_t *hot_rows, int64_
     h->table = table->dev;
     h->N = table->N;
     h->D = table->D;
+    h->pitch = table->pitch;
     h->elem = table->elem;
     h->n_hot = n_hot;
     int64_t *ids_dev = nullptr;
@@ -489,8 +517,8 @@ ud_status ud_cache_create(const ud_table *table, const int64_t *hot_rows, int64_
         st = hip_fail(e, "ud_cache_create");
     // the cache is filled by the library's own zero-copy gather, then the map is scattered
     if (st == UD_OK)
-        st = gather_impl(table->dev, table->N, table->D, table->elem, ids_dev, UD_I64, n_hot, h->rows, nullptr, nullptr,
-                         nullptr, nullptr);
+        st = gather_impl(table->dev, table->N, table->D, table->pitch, table->elem, ids_dev, UD_I64, n_hot, h->rows, nullptr,
+                         nullptr, nullptr, nullptr);
     if (st == UD_OK) {
         e = ud::launch_fill_slots(ids_dev, n_hot, h->slot, nullptr);
         if (e == hipSuccess)
@@ -530,7 +558,7 @@ ud_status ud_gather_cached(const ud_cache *c, ud_dtype dtype, const void *idx, u
     // the table's storage type must match the gather's input type
     if ((dtype == UD_F32) != (c->elem == UD_F32))
         return UD_ERR_INVALID_ARG;
-    return gather_impl(c->table, c->N, c->D, dtype, idx, itype, M, out, stream, nullptr, c->slot,
+    return gather_impl(c->table, c->N, c->D, c->pitch, dtype, idx, itype, M, out, stream, nullptr, c->slot,
                        static_cast<const char *>(c->rows));
 }
 

@@ -92,7 +92,7 @@ __device__ __forceinline__ const char *row_source(const GatherArgs &a, int64_t r
         if (s >= 0)
             return a.cache + static_cast<int64_t>(s) * row_bytes;
     }
-    return a.table + r * row_bytes;
+    return a.table + r * a.pitch_bytes;
 }
 
 // Exact binary16 -> binary32.  The hardware converter widens every finite

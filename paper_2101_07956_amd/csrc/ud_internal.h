@@ -14,6 +14,7 @@ constexpr unsigned long long kNoBadIndex = 0x7fffffffffffffffull;
 struct GatherArgs {
     const char *table;       // device pointer to row 0
     int64_t N, D;
+    int64_t pitch_bytes;     // distance between table rows in bytes (>= D * element size)
     const void *idx;         // device pointer, M entries
     int itype;               // UD_I64 / UD_I32
     int64_t M;

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kBlockThreads) void scatter_chunked(GatherArgs a, i
                     if (l == 0)
                         atomicMin(a.err, static_cast<unsigned long long>(i[u]));
                 } else {
-                    char *dst = table + r * row_bytes;
+                    char *dst = table + r * a.pitch_bytes;
                     head[u] = static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 15u);
                     base[u] = dst - head[u];
                     nch[u] = (head[u] + row_bytes + 15) >> 4;

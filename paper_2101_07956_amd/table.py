@@ -19,6 +19,7 @@ class Table:
     def __init__(self, N: int, D: int, elem: int = B.UD_F32, flags: int = B.UD_TABLE_COHERENT, _handle=None):
         self.handle = _handle if _handle is not None else B.ud_alloc_table(N, D, elem, flags)
         self.N, self.D, self.elem = B.ud_table_shape(self.handle)
+        self.pitch = B.ud_table_pitch(self.handle)          # elements between rows (> D for padded tables)
         self.device_ptr = B.ud_table_device_ptr(self.handle)
         self.host_ptr = B.ud_table_host_ptr(self.handle)
 
@@ -28,14 +29,15 @@ class Table:
 
     @property
     def nbytes(self) -> int:
-        return self.N * self.D * self.elem_bytes
+        return self.N * self.pitch * self.elem_bytes
 
     def numpy(self) -> np.ndarray:
-        """The CPU's view of a host table (no copy): the CPU uses it like ordinary memory."""
+        """The CPU's view of a host table (no copy): the CPU uses it like ordinary memory.
+        For a padded table this is the [N, D] data window of the [N, pitch] storage."""
         if not self.host_ptr:
             raise ValueError("device-resident table has no host view")
         buf = (ctypes.c_char * self.nbytes).from_address(self.host_ptr)
-        return np.frombuffer(buf, dtype=_ELEM_NP[self.elem]).reshape(self.N, self.D)
+        return np.frombuffer(buf, dtype=_ELEM_NP[self.elem]).reshape(self.N, self.pitch)[:, : self.D]
 
     def to_device(self, row0: int = 0, n: int | None = None) -> "Table":
         n = self.N - row0 if n is None else n
@@ -96,8 +98,13 @@ def gather(table: Table, idx, out=None, widen: bool = False, tuning: B.ud_tuning
         out = torch.empty((M, table.D), dtype=odt, device=idx.device)
     assert out.is_cuda and out.is_contiguous() and out.dtype == odt and out.numel() == M * table.D
     stream = torch.cuda.current_stream(idx.device).cuda_stream
-    B.ud_gather_tuned(table.device_ptr, table.N, table.D, dtype, idx.data_ptr(), itype, M,
-                      out.data_ptr(), stream, tuning)
+    if table.pitch != table.D:
+        assert tuning is None, "explicit tuning is for dense tables"
+        B.ud_gather_pitched(table.device_ptr, table.N, table.D, table.pitch, dtype, idx.data_ptr(), itype, M,
+                            out.data_ptr(), stream)
+    else:
+        B.ud_gather_tuned(table.device_ptr, table.N, table.D, dtype, idx.data_ptr(), itype, M,
+                          out.data_ptr(), stream, tuning)
     if check:
         B.ud_gather_status(stream)
     return out

@@ -98,7 +98,9 @@ def test_table_calls_reject_bad_arguments(ud):
     assert rs("ud_alloc_table", 0, 4, 0, 0, ctypes.byref(t)) == inv
     assert rs("ud_alloc_table", 4, 0, 0, 0, ctypes.byref(t)) == inv
     assert rs("ud_alloc_table", 4, 4, 2, 0, ctypes.byref(t)) == inv      # UD_F16_TO_F32 is not a storage type
-    assert rs("ud_alloc_table", 4, 4, 0, 2, ctypes.byref(t)) == inv      # unknown flag
+    assert rs("ud_alloc_table", 4, 4, 0, 4, ctypes.byref(t)) == inv      # unknown flag
+    assert rs("ud_table_pitch", None, None) == inv
+    assert rs("ud_gather_pitched", 0x1000, 4, 8, 7, 0, 0x2000, 0, 1, 0x3000, None) == inv   # pitch < D
     assert rs("ud_alloc_table", 4, 4, 0, 0, None) == inv
     assert rs("ud_alloc_table", 2**40, 2**30, 0, 0, ctypes.byref(t)) == inv
     assert rs("ud_table_to_device", None, 0, 1, ctypes.byref(t)) == inv

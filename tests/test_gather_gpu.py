@@ -4,6 +4,7 @@ Bit-exact comparison (integer/bit work: the gather copies patterns, the
 widening is exact), on seeded inputs that span several wavefront batches and a
 ragged tail, for every kernel instantiation the library can select.
 """
+import ctypes
 import itertools
 
 import numpy as np
@@ -551,4 +552,57 @@ def test_torch_convenience_wrapper(ud):
     with pytest.raises(ValueError):
         t.to_device().numpy()
     h.free()
+    t.free()
+
+
+# ---- padded tables: row pitch rounded up to 128 bytes ----
+
+@pytest.mark.parametrize("elem_name,dtype_name,D", [("UD_F32", "UD_F32", 1), ("UD_F32", "UD_F32", 100), ("UD_F32", "UD_F32", 602),
+                                                     ("UD_F32", "UD_F32", 128), ("UD_F16", "UD_F16_TO_F32", 602),
+                                                     ("UD_F16", "UD_F16", 301)])
+def test_padded_table(ud, elem_name, dtype_name, D):
+    elem, dtype = getattr(ud, elem_name), getattr(ud, dtype_name)
+    N, M = 4001, 5003
+    t = ud.Table(N, D, elem, ud.UD_TABLE_PAD_ROWS)
+    per_line = 128 // t.elem_bytes
+    assert t.pitch == -(-D // per_line) * per_line and t.pitch >= D and t.device_ptr % 128 == 0
+    # fill data and padding alike, then poison the padding: it must never reach the output
+    if elem == ud.UD_F32:
+        workloads.fill_uniform_f32(t.host_ptr, 40, N * t.pitch)
+    else:
+        workloads.fill_normal_f16(t.host_ptr, 40, N * t.pitch)
+    storage = np.frombuffer((ctypes.c_char * t.nbytes).from_address(t.host_ptr),
+                            dtype=np.uint32 if elem == ud.UD_F32 else np.uint16).reshape(N, t.pitch)
+    storage[:, D:] = 0xFFFF
+    idx = workloads.indices_uniform(41, M, N)
+    idx[:2] = [0, N - 1]
+    obytes = 2 if dtype == ud.UD_F16 else 4
+    want = np.empty((M, D), dtype=np.uint16 if obytes == 2 else np.uint32)
+    oracle.gather_raw(t.host_ptr, N, D, dtype, idx, want, pitch=t.pitch)
+    assert np.array_equal(np.take(storage, idx, axis=0)[:, :D], want) or dtype == ud.UD_F16_TO_F32
+    for table in (t, t.to_device()):
+        buf = torch.full(((M * D + 64) * obytes,), CANARY, dtype=torch.uint8, device="cuda")
+        didx = torch.from_numpy(idx).cuda()
+        s = torch.cuda.current_stream().cuda_stream
+        ud.ud_gather_pitched(table.device_ptr, N, D, table.pitch, dtype, didx.data_ptr(), ud.UD_I64, M, buf.data_ptr(), s)
+        ud.ud_gather_status(s)
+        host = buf.cpu().numpy()
+        assert (host[M * D * obytes:] == CANARY).all()
+        assert np.array_equal(host[: M * D * obytes].view(want.dtype).reshape(M, D), want), (D, table.host_ptr != 0)
+    # the hot-row cache works on padded tables too
+    c = ud.Cache(t, np.arange(0, N, 2, dtype=np.int64))
+    assert np.array_equal(run_cached(ud, c, dtype, idx, D), want)
+    c.free()
+    t.free()
+
+
+def test_padded_table_through_the_torch_wrapper(ud):
+    N, D, M = 3000, 602, 2000
+    t = ud.Table(N, D, ud.UD_F32, ud.UD_TABLE_PAD_ROWS)
+    assert t.pitch == 608
+    data = workloads.uniform_f32(42, N, D)
+    t.numpy()[:] = data                                           # the [N, D] window of the padded storage
+    idx_np = workloads.indices_uniform(43, M, N)
+    out = ud.gather(t, torch.from_numpy(idx_np).cuda(), check=True)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), oracle.gather(data, idx_np).view(np.uint32))
     t.free()
