@@ -787,6 +787,18 @@ def main() -> int:
         for D in WIDTHS
     }
 
+    # ---- secondary timing: call to stream-sync per gather, including the ID list's host-to-device copy ----
+    pinned_ids = [torch.from_numpy(ids_host[s]).pin_memory() for s in range(W + K)]
+    wall = {}
+    for D in WIDTHS:
+        ms = _wall_times(ud, torch, table.device_ptr, N_ROWS, D, ud.UD_F32, pinned_ids, out, W)
+        st = _stats(ms)
+        wall[str(D)] = {"median_ms": st["median_ms"], "min_ms": st["min_ms"],
+                        "GBps": round(M_ROWS * D * 4 / st["median_ms"] / 1e6, 2)}
+    del pinned_ids
+    step(W + K - 1, table.device_ptr)            # leave the last step's D=602 result in `out` for the spot check
+    torch.cuda.synchronize()
+
     # ---- parity spot check of the last step's last gather against the oracle (outside the timed region) ----
     import oracle
     sample = np.random.default_rng(0).choice(M_ROWS, 4096, replace=False)
@@ -877,6 +889,7 @@ def main() -> int:
         "rows_per_s": round(rows_per_s),
         "h2d_peak_GBps": round(h2d_peak, 2),
         "per_width": per_width,
+        "call_to_sync_incl_id_copy": wall,
         "parity_spot_check": parity_ok,
         "roofline": {"bound": "host_link", "kernel": "gather_chunked<f32> D=602 (2408-byte rows)",
                      "achieved": round(dom_achieved, 2), "peak": round(h2d_peak, 2), "unit": "GB/s",

@@ -24,8 +24,11 @@ def __getattr__(name: str):
         return importlib.import_module("." + name, __name__)
     binding = importlib.import_module(".binding", __name__)
     if hasattr(binding, name):
-        return getattr(binding, name)
-    table = importlib.import_module(".table", __name__)
-    if hasattr(table, name):
-        return getattr(table, name)
-    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
+        value = getattr(binding, name)
+    else:
+        table = importlib.import_module(".table", __name__)
+        if not hasattr(table, name):
+            raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
+        value = getattr(table, name)
+    globals()[name] = value          # resolved once: later look-ups do not come through here
+    return value
