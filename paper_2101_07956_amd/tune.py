@@ -8,7 +8,7 @@ run for the host link, the chip's published HBM peak for the device-resident var
 prints, per width and residence, the best shapes, the shape ``ud_gather`` picks by itself, and how
 far apart they are; ``--json FILE`` also writes every measurement.
 
-    python -m paper_2101_07956_amd.tune --amplification gpurun_out/prof_fetch/fetch_counter_collection.csv \
+    python -m paper_2101_07956_amd.tune --amplification prof_fetch/fetch_counter_collection.csv \
         --rows 1000000 --scale 2.0
 
 turns a ``rocprofv3 --pmc FETCH_SIZE`` (or ``WRITE_SIZE``) counter file of a ``bench.py`` run into bytes

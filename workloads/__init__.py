@@ -183,6 +183,8 @@ def sample_procedural(N: int, degree: int, alpha: float, graph_seed: int, nseeds
     return out[:n].copy()
 
 
-#: the two GraphSAGE-style workloads: graph and sampling parameters (see the design doc for why alpha differs)
+#: the two GraphSAGE-style workloads: graph and sampling parameters.  alpha (neighbour popularity ~ rank**-alpha)
+#: is set so that a de-duplicated minibatch holds about 200K (products-like) and 500K (papers-like) IDs; with
+#: alpha = 1.0 the batches would be several times smaller
 PRODUCTS_LIKE = dict(N=2_400_000, D=100, mean_degree=50, dmin=25, alpha=0.6, nseeds=1024, fanout=(25, 10))
 PAPERS_LIKE = dict(N=111_000_000, D=256, degree=30, alpha=0.8, nseeds=1024, fanout=(15, 10, 5))
