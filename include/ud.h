@@ -124,6 +124,9 @@ ud_status ud_free_table(ud_table *t);
  * int64), UD_ERR_HIP (launch failure).
  * The library allocates nothing per call; the first call on a device allocates
  * one 8-byte error word in HBM that lives until the process ends.
+ * For tuning runs the environment variable UD_GATHER_TUNING =
+ * "lanes,chunks,rows,max_blocks,flags" (see ud_tuning; 0 = automatic) makes this
+ * call use those kernel parameters; it is read once per process.
  */
 ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
                     const void *idx, ud_itype itype, int64_t M,

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -162,6 +163,30 @@ ud::Plan auto_plan(const void *table, int64_t D, int64_t pitch, ud_dtype dtype)
 }
 
 bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// UD_GATHER_TUNING="lanes,chunks,rows,max_blocks,flags" (any field may be 0 = automatic) makes
+// ud_gather behave like ud_gather_tuned with those parameters: an A/B switch for tuning runs that
+// needs no change in the caller.  Read once per process; malformed values are ignored.
+const ud_tuning *env_tuning()
+{
+    static const ud_tuning *cached = []() -> const ud_tuning * {
+        const char *v = std::getenv("UD_GATHER_TUNING");
+        if (!v || !*v)
+            return nullptr;
+        static ud_tuning t{};
+        int lanes = 0, chunks = 0, rows = 0, blocks = 0;
+        unsigned flags = 0;
+        if (std::sscanf(v, "%d,%d,%d,%d,%u", &lanes, &chunks, &rows, &blocks, &flags) != 5)
+            return nullptr;
+        t.lanes_per_row = lanes;
+        t.chunks_per_lane = chunks;
+        t.rows_in_flight = rows;
+        t.max_blocks = blocks;
+        t.flags = flags;
+        return &t;
+    }();
+    return cached;
+}
 
 } // namespace
 
@@ -411,7 +436,7 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
                     const void *idx, ud_itype itype, int64_t M,
                     void *out, void *stream)
 {
-    return gather_impl(table, N, D, D, dtype, idx, itype, M, out, stream, nullptr, nullptr, nullptr);
+    return gather_impl(table, N, D, D, dtype, idx, itype, M, out, stream, env_tuning(), nullptr, nullptr);
 }
 
 ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,

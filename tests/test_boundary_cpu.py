@@ -137,3 +137,19 @@ def test_header_is_plain_c_and_the_library_links_from_c(ud, tmp_path):
                            "-o", exe, "-L", pkg, "-lud", "-Wl,-rpath," + pkg])
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0 and "c abi ok" in r.stdout, (r.returncode, r.stdout, r.stderr)
+
+
+def test_environment_override_reaches_ud_gather():
+    # UD_GATHER_TUNING makes ud_gather validate (and use) explicit kernel parameters: an unsupported
+    # combination is refused, where the same call without the variable is accepted
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "import paper_2101_07956_amd as ud\n"
+            "print(ud.binding.raw_status('ud_gather', 0x1000, 10, 4, 0, 0x2000, 0, 0, 0x3000, None))\n" % ROOT)
+    plain = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env={**os.environ})
+    forced = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True,
+                            env={**os.environ, "UD_GATHER_TUNING": "64,4,4,0,0"})
+    garbage = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True,
+                             env={**os.environ, "UD_GATHER_TUNING": "fast please"})
+    assert plain.stdout.strip() == "0" and forced.stdout.strip() == "2" and garbage.stdout.strip() == "0"
