@@ -886,6 +886,8 @@ def main() -> int:
                                "one step = one gather per width",
                    "table": "pinned host memory (zero-copy)", "N": N_ROWS, "M": M_ROWS, "widths": list(WIDTHS)},
         "frac_of_h2d_peak": round(value / h2d_peak, 4),
+        "min_frac_of_h2d_peak_rows_ge_512B": min(per_width[str(D)]["frac_of_h2d_peak"] for D in WIDTHS if D * 4 >= 512),
+        "theoretical_link_GBps": 63.0,          # PCIe Gen5 x16 after 128b/130b encoding, before packet overhead: context only
         "rows_per_s": round(rows_per_s),
         "h2d_peak_GBps": round(h2d_peak, 2),
         "per_width": per_width,
