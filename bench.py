@@ -223,6 +223,9 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
         ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
         cap = max(a.size for a in ids_np)
         out = torch.empty(cap * D, dtype=torch.float32, device=dev)
+        sorted_dev = [torch.from_numpy(np.sort(a)).to(dev) for a in ids_np]      # secondary: the same IDs in ascending order
+        kern_sorted = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, sorted_dev[:W] + sorted_dev, out, W)
+        del sorted_dev
         kern = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev[:W] + ids_dev, out, W)
         ok = spot_check(table, N, D, oracle.F32, ids_np[-1], out)
         padded = [pinned(a) for a in ids_np]
@@ -243,6 +246,7 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                                    "CSR graph (mean degree 50), 1,024 seeds, fanout [25,10], de-duplicated; 100 batches; one step = one batch",
                        "unique_ids_per_batch": [min(sizes), max(sizes)]},
                       kernel_only=_stats(kern), call_to_sync_incl_id_copy=_stats(wall),
+                      sorted_ids_GBps=round(total_bytes / sum(kern_sorted) / 1e6, 2),
                       wall_GBps=round(total_bytes / sum(wall) / 1e6, 2), rows_per_s=round(sum(sizes) / sum(kern) * 1e3),
                       cpu_centric=extra or None, parity_spot_check=ok)
 
@@ -256,6 +260,9 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
         ids_dev = [torch.from_numpy(a).to(dev) for a in ids_np]
         cap = max(a.size for a in ids_np)
         out = torch.empty(cap * D, dtype=torch.float32, device=dev)
+        sorted_dev = [torch.from_numpy(np.sort(a)).to(dev) for a in ids_np]
+        kern_sorted = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, sorted_dev[:W] + sorted_dev, out, W)
+        del sorted_dev
         kern = _kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev[:W] + ids_dev, out, W)
         ok = spot_check(table, N, D, oracle.F32, ids_np[-1], out)
         total_bytes = sum(a.size for a in ids_np) * D * 4
@@ -277,6 +284,7 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                                    "exceed what hipHostMalloc grants on this box), procedural Zipf graph, 1,024 seeds, fanout "
                                    "[15,10,5], de-duplicated; one step = one batch", "unique_ids_per_batch": [min(sizes), max(sizes)]},
                       kernel_only=_stats(kern), rows_per_s=round(sum(sizes) / sum(kern) * 1e3),
+                      sorted_ids_GBps=round(total_bytes / sum(kern_sorted) / 1e6, 2),
                       device_resident_slice={"rows": srows, "GBps_read_plus_write": round(hbm_bytes / sum(kern_h) / 1e6, 1),
                                              "frac_of_8TBps": round(hbm_bytes / sum(kern_h) / 1e6 / HBM_PEAK_GBPS, 4),
                                              "kernel_only": _stats(kern_h)},
