@@ -907,6 +907,10 @@ def main() -> int:
                      "traffic_unit": "bytes per launch (L2<->fabric reads + writes, rocprofv3 FETCH_SIZE/WRITE_SIZE)",
                      "algorithmic_bytes_per_launch": M_ROWS * (2 * 602 * 4 + 8),
                      "link_bytes_per_launch": M_ROWS * 602 * 4,
+                     # a dense table of 2408-byte rows makes a row overlap 19.75 128-byte lines on average (the
+                     # hardware fetches whole lines): the most a gather of this layout can show is 2408 / 2528 of the peak
+                     "line_floor_bytes_per_launch": int(M_ROWS * 19.75 * 128),
+                     "frac_incl_line_padding": round(M_ROWS * 19.75 * 128 / dom_ms / 1e6 / h2d_peak, 4),
                      "peak_source": "best of 10 pinned hipMemcpy H2D of 1 GiB in this run",
                      "ms_per_launch": round(dom_ms, 4)},
         "roofline_hbm": {"bound": "hbm", "kernel": "gather_chunked<f32> D=602, table in HBM",
