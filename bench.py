@@ -506,6 +506,9 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                           ("64wg_4rows_in_flight", ud.ud_tuning(0, 1, 4, 64, 0)),
                           ("32wg_4rows_in_flight", ud.ud_tuning(0, 1, 4, 32, 0)),
                           ("128wg_priority", ud.ud_tuning(0, 0, 0, 128, ud.UD_TUNE_WAVE_PRIORITY)),
+                          ("128wg_streaming_loads", ud.ud_tuning(0, 0, 0, 128, ud.UD_TUNE_NT_LOAD | ud.UD_TUNE_NT_STORE)),
+                          ("64wg_streaming_loads", ud.ud_tuning(0, 0, 0, 64, ud.UD_TUNE_NT_LOAD | ud.UD_TUNE_NT_STORE)),
+                          ("share_gpu_flag", ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU)),
                           ("32wg_of_1024", ud.ud_tuning(0, 0, 0, 32, ud.UD_TUNE_BIG_BLOCKS)),
                           ("16wg_of_1024", ud.ud_tuning(0, 0, 0, 16, ud.UD_TUNE_BIG_BLOCKS)),
                           ("16wg_of_1024_2rows", ud.ud_tuning(0, 1, 2, 16, ud.UD_TUNE_BIG_BLOCKS)),
