@@ -68,6 +68,12 @@ def _load():
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
             ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
         ]
+        lib.oracle_scatter_pitched.restype = ctypes.c_int
+        lib.oracle_scatter_pitched.argtypes = [
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+            ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
+        ]
         lib.oracle_count_requests.restype = ctypes.c_int64
         lib.oracle_count_requests.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
@@ -125,13 +131,15 @@ def gather(table: np.ndarray, idx: np.ndarray, dtype: int | None = None) -> np.n
     return out.view(table.dtype)
 
 
-def scatter_raw(table_ptr: int, N: int, D: int, dtype: int, idx: np.ndarray, src: np.ndarray) -> None:
-    """Oracle scatter into a table at a raw host address: ``table[idx[i], :] = src[i, :]``, in order of i."""
+def scatter_raw(table_ptr: int, N: int, D: int, dtype: int, idx: np.ndarray, src: np.ndarray,
+                pitch: int | None = None) -> None:
+    """Oracle scatter into a table at a raw host address: ``table[idx[i], :] = src[i, :]``, in order of i.
+    ``pitch`` is the distance between table rows in elements (default ``D``)."""
     itype = {np.dtype(np.int64): I64, np.dtype(np.int32): I32}[idx.dtype]
     assert idx.flags.c_contiguous and src.flags.c_contiguous
     bad = ctypes.c_int64(-1)
-    rc = _load().oracle_scatter(table_ptr, N, D, dtype, idx.ctypes.data, itype, idx.size,
-                                src.ctypes.data, ctypes.byref(bad))
+    rc = _load().oracle_scatter_pitched(table_ptr, N, D, D if pitch is None else pitch, dtype, idx.ctypes.data, itype,
+                                        idx.size, src.ctypes.data, ctypes.byref(bad))
     if rc == ERR_INDEX:
         raise OracleIndexError(bad.value)
     if rc != OK:

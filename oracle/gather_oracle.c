@@ -238,13 +238,26 @@ int64_t oracle_circular_shift(int64_t i, int64_t r, int64_t D, int64_t elems_per
  * All IDs are checked before anything is written; on a bad ID *bad_pos is its
  * first position, ORACLE_ERR_INDEX is returned and the table is untouched.
  */
+int oracle_scatter_pitched(void *table, int64_t N, int64_t D, int64_t pitch, int dtype,
+                           const void *idx, int itype, int64_t M,
+                           const void *src, int64_t *bad_pos);
+
 int oracle_scatter(void *table, int64_t N, int64_t D, int dtype,
                    const void *idx, int itype, int64_t M,
                    const void *src, int64_t *bad_pos)
 {
+    return oracle_scatter_pitched(table, N, D, D, dtype, idx, itype, M, src, bad_pos);
+}
+
+/* The same with table rows `pitch` elements apart (pitch >= D): table[idx[i]*pitch + j] = src[i*D + j];
+ * the padding elements D..pitch-1 of every row are never written. */
+int oracle_scatter_pitched(void *table, int64_t N, int64_t D, int64_t pitch, int dtype,
+                           const void *idx, int itype, int64_t M,
+                           const void *src, int64_t *bad_pos)
+{
     if (bad_pos)
         *bad_pos = -1;
-    if (N < 1 || D < 1 || M < 0)
+    if (N < 1 || D < 1 || M < 0 || pitch < D)
         return ORACLE_ERR_INVALID_ARG;
     if (dtype != ORACLE_F32 && dtype != ORACLE_F16)
         return ORACLE_ERR_INVALID_ARG;
@@ -267,9 +280,9 @@ int oracle_scatter(void *table, int64_t N, int64_t D, int dtype,
         const int64_t r = read_index(idx, itype, i);
         for (int64_t j = 0; j < D; ++j) {
             if (dtype == ORACLE_F32)
-                ((uint32_t *)table)[r * D + j] = ((const uint32_t *)src)[i * D + j];
+                ((uint32_t *)table)[r * pitch + j] = ((const uint32_t *)src)[i * D + j];
             else
-                ((uint16_t *)table)[r * D + j] = ((const uint16_t *)src)[i * D + j];
+                ((uint16_t *)table)[r * pitch + j] = ((const uint16_t *)src)[i * D + j];
         }
     }
     return ORACLE_OK;

@@ -74,3 +74,15 @@ def test_empty_scatter_is_a_no_op():
     before = table.copy()
     oracle.scatter(table, np.empty(0, dtype=np.int64), np.empty((0, 4), dtype=np.float32))
     assert np.array_equal(table, before)
+
+
+@pytest.mark.parametrize("D,pitch", [(3, 8), (100, 128), (602, 608), (7, 7)])
+def test_pitched_scatter_matches_numpy_and_leaves_the_padding_alone(D, pitch):
+    N, M = 400, 250
+    padded = workloads.uniform_f32(31, N, pitch)
+    want = padded.copy()
+    idx = np.random.default_rng(32).permutation(N)[:M].astype(np.int64)
+    src = workloads.uniform_f32(33, M, D)
+    oracle.scatter_raw(padded.ctypes.data, N, D, oracle.F32, idx, src, pitch=pitch)
+    want[idx, :D] = src
+    assert np.array_equal(padded.view(np.uint32), want.view(np.uint32))
