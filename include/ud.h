@@ -241,6 +241,10 @@ ud_status ud_gather_tuned(const void *table, int64_t N, int64_t D, ud_dtype dtyp
 ud_status ud_scatter(void *table, int64_t N, int64_t D, ud_dtype dtype,
                      const void *idx, ud_itype itype, int64_t M,
                      const void *src, void *stream);
+/* ud_scatter into a table whose rows are `pitch` elements apart (UD_TABLE_PAD_ROWS); the padding is never written. */
+ud_status ud_scatter_pitched(void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
+                             const void *idx, ud_itype itype, int64_t M,
+                             const void *src, void *stream);
 /* ud_scatter with explicit kernel parameters (tuning->flags must be 0). */
 ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
                            const void *idx, ud_itype itype, int64_t M,

@@ -29,7 +29,7 @@ EXPORTS = (
     "ud_alloc_table", "ud_table_to_device", "ud_table_host_ptr", "ud_table_device_ptr",
     "ud_table_shape", "ud_table_pitch", "ud_free_table", "ud_gather", "ud_gather_pitched", "ud_gather_tuned", "ud_gather_plan",
     "ud_gather_status", "ud_cache_create", "ud_cache_free", "ud_gather_cached",
-    "ud_scatter", "ud_scatter_tuned", "ud_status_str", "ud_last_hip_error",
+    "ud_scatter", "ud_scatter_tuned", "ud_scatter_pitched", "ud_status_str", "ud_last_hip_error",
 )
 
 
@@ -80,6 +80,7 @@ _lib.ud_gather_tuned.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _v
 _lib.ud_gather_plan.argtypes = [_vp, _i64, _int, ctypes.POINTER(ud_tuning)]
 _lib.ud_gather_status.argtypes = [_vp, ctypes.POINTER(_i64)]
 _lib.ud_scatter.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
+_lib.ud_scatter_pitched.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_scatter_tuned.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp, ctypes.POINTER(ud_tuning)]
 _lib.ud_cache_create.argtypes = [_vp, _vp, _i64, ctypes.POINTER(_vp)]
 _lib.ud_cache_free.argtypes = [_vp]
@@ -187,6 +188,12 @@ def ud_scatter(table: int, N: int, D: int, dtype: int, idx: int, itype: int, M: 
         _check(_lib.ud_scatter(table, N, D, dtype, idx, itype, M, src, stream), "ud_scatter")
     else:
         _check(_lib.ud_scatter_tuned(table, N, D, dtype, idx, itype, M, src, stream, ctypes.byref(tuning)), "ud_scatter_tuned")
+
+
+def ud_scatter_pitched(table: int, N: int, D: int, pitch: int, dtype: int, idx: int, itype: int, M: int, src: int,
+                       stream: int | None = None) -> None:
+    """``ud_scatter`` into a table whose rows are ``pitch`` elements apart."""
+    _check(_lib.ud_scatter_pitched(table, N, D, pitch, dtype, idx, itype, M, src, stream), "ud_scatter_pitched")
 
 
 def ud_cache_create(table: int, hot_rows_host_ptr: int, n_hot: int) -> int:

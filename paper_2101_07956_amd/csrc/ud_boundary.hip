@@ -439,22 +439,22 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
     return gather_impl(table, N, D, D, dtype, idx, itype, M, out, stream, env_tuning(), nullptr, nullptr);
 }
 
-ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
-                           const void *idx, ud_itype itype, int64_t M,
-                           const void *src, void *stream, const ud_tuning *tuning)
+static ud_status scatter_impl(void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
+                              const void *idx, ud_itype itype, int64_t M,
+                              const void *src, void *stream, const ud_tuning *tuning)
 {
-    if (N < 1 || D < 1 || M < 0)
+    if (N < 1 || D < 1 || M < 0 || pitch < D)
         return UD_ERR_INVALID_ARG;
     if (dtype != UD_F32 && dtype != UD_F16)
         return UD_ERR_INVALID_ARG;
     if (itype != UD_I64 && itype != UD_I32)
         return UD_ERR_INVALID_ARG;
     int64_t table_bytes, src_bytes;
-    if (mul3_overflows(N, D, elem_bytes(dtype), &table_bytes) || mul3_overflows(M, D, elem_bytes(dtype), &src_bytes))
+    if (mul3_overflows(N, pitch, elem_bytes(dtype), &table_bytes) || mul3_overflows(M, D, elem_bytes(dtype), &src_bytes))
         return UD_ERR_INVALID_ARG;
     if (table_bytes > INT64_MAX - 64)
         return UD_ERR_INVALID_ARG;
-    ud::Plan plan = auto_plan(table, D, D, dtype);
+    ud::Plan plan = auto_plan(table, D, pitch, dtype);
     plan.flags = 0;
     if (tuning) {
         if (tuning->flags)
@@ -491,7 +491,7 @@ ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
     a.itype = itype;
     a.M = M;
     a.out = const_cast<void *>(src);
-    a.pitch_bytes = D * elem_bytes(dtype);
+    a.pitch_bytes = pitch * elem_bytes(dtype);
     const ud_status es = error_word(&a.err);
     if (es != UD_OK)
         return es;
@@ -503,11 +503,25 @@ ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
     return UD_OK;
 }
 
+ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
+                           const void *idx, ud_itype itype, int64_t M,
+                           const void *src, void *stream, const ud_tuning *tuning)
+{
+    return scatter_impl(table, N, D, D, dtype, idx, itype, M, src, stream, tuning);
+}
+
 ud_status ud_scatter(void *table, int64_t N, int64_t D, ud_dtype dtype,
                      const void *idx, ud_itype itype, int64_t M,
                      const void *src, void *stream)
 {
-    return ud_scatter_tuned(table, N, D, dtype, idx, itype, M, src, stream, nullptr);
+    return scatter_impl(table, N, D, D, dtype, idx, itype, M, src, stream, nullptr);
+}
+
+ud_status ud_scatter_pitched(void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
+                             const void *idx, ud_itype itype, int64_t M,
+                             const void *src, void *stream)
+{
+    return scatter_impl(table, N, D, pitch, dtype, idx, itype, M, src, stream, nullptr);
 }
 
 ud_status ud_cache_create(const ud_table *table, const int64_t *hot_rows, int64_t n_hot, ud_cache **c)

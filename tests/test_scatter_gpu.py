@@ -152,3 +152,26 @@ def test_empty_scatter(ud):
     ud.ud_gather_status(None)
     assert np.array_equal(t.numpy(), before)
     t.free()
+
+
+@pytest.mark.parametrize("elem_name,D", [("UD_F32", 100), ("UD_F32", 602), ("UD_F16", 301)])
+def test_scatter_into_padded_table(ud, elem_name, D):
+    import ctypes
+    elem = getattr(ud, elem_name)
+    N, M = 3001, 1500
+    t = ud.Table(N, D, elem, ud.UD_TABLE_PAD_ROWS)
+    storage = np.frombuffer((ctypes.c_char * t.nbytes).from_address(t.host_ptr),
+                            dtype=np.uint32 if elem == ud.UD_F32 else np.uint16).reshape(N, t.pitch)
+    storage[:] = np.random.default_rng(D).integers(0, 60000, size=storage.shape).astype(storage.dtype)
+    want = storage.copy()
+    idx = distinct_ids(D, M, N)
+    src = (workloads.uniform_f32(5, M, D) if elem == ud.UD_F32 else workloads.normal_f16(5, M, D))
+    oracle.scatter_raw(want.ctypes.data, N, D, oracle.F32 if elem == ud.UD_F32 else oracle.F16, idx,
+                       np.ascontiguousarray(src), pitch=t.pitch)
+    dsrc = torch.from_numpy(src.view(np.int32 if elem == ud.UD_F32 else np.int16)).cuda()
+    didx = torch.from_numpy(idx).cuda()
+    s = torch.cuda.current_stream().cuda_stream
+    ud.ud_scatter_pitched(t.device_ptr, N, D, t.pitch, elem, didx.data_ptr(), ud.UD_I64, M, dsrc.data_ptr(), s)
+    ud.ud_gather_status(s)
+    assert np.array_equal(storage, want)                      # data rows updated, padding and other rows untouched
+    t.free()
