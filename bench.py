@@ -505,9 +505,6 @@ def run_other(args, ud, bl, workloads, torch, np, threads, ncores) -> int:
                           ("128wg", ud.ud_tuning(0, 0, 0, 128, 0)), ("64wg", ud.ud_tuning(0, 0, 0, 64, 0)),
                           ("64wg_4rows_in_flight", ud.ud_tuning(0, 1, 4, 64, 0)),
                           ("32wg_4rows_in_flight", ud.ud_tuning(0, 1, 4, 32, 0)),
-                          ("128wg_priority", ud.ud_tuning(0, 0, 0, 128, ud.UD_TUNE_WAVE_PRIORITY)),
-                          ("128wg_streaming_loads", ud.ud_tuning(0, 0, 0, 128, ud.UD_TUNE_NT_LOAD | ud.UD_TUNE_NT_STORE)),
-                          ("64wg_streaming_loads", ud.ud_tuning(0, 0, 0, 64, ud.UD_TUNE_NT_LOAD | ud.UD_TUNE_NT_STORE)),
                           ("share_gpu_flag", ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU)),
                           ("32wg_of_1024", ud.ud_tuning(0, 0, 0, 32, ud.UD_TUNE_BIG_BLOCKS)),
                           ("16wg_of_1024", ud.ud_tuning(0, 0, 0, 16, ud.UD_TUNE_BIG_BLOCKS)),
@@ -721,9 +718,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    if not os.path.exists(os.path.join(ROOT, "paper_2101_07956_amd", "libud.so")):
-        from paper_2101_07956_amd import build as hip_build      # nothing built yet: build, else load what is there
-        hip_build.build(verbose=False)
+    from paper_2101_07956_amd import build as hip_build
+    hip_build.ensure_built()            # builds only if no library is there or its stamp differs from the sources
     import paper_2101_07956_amd as ud
     import workloads
 

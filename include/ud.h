@@ -123,7 +123,10 @@ ud_status ud_free_table(ud_table *t);
  * NULL or misaligned pointer with M > 0, sizes whose byte counts overflow
  * int64), UD_ERR_HIP (launch failure).
  * The library allocates nothing per call; the first call on a device allocates
- * one 8-byte error word in HBM that lives until the process ends.
+ * a 512-byte table of ID-error slots in HBM (one slot per stream, see
+ * ud_gather_status) that lives until the process ends.  That first call copies
+ * the table's initial contents synchronously, so it must not happen under
+ * stream capture: run one gather eagerly before capturing gathers in a HIP graph.
  * For tuning runs the environment variable UD_GATHER_TUNING =
  * "lanes,chunks,rows,max_blocks,flags" (see ud_tuning; 0 = automatic) makes this
  * call use those kernel parameters; it is read once per process.
@@ -172,9 +175,12 @@ ud_status ud_gather_cached(const ud_cache *c, ud_dtype dtype, const void *idx, u
                            void *out, void *stream);
 
 /*
- * Kernel tuning for ud_gather_tuned; a zero field means "choose automatically".
+ * Kernel tuning for ud_gather_tuned.  A zero in one of the first four fields means "choose
+ * automatically"; `flags` is taken literally (0 = none of the options; the automatic choice of flags
+ * for a table is what ud_gather_plan returns).
  *   lanes_per_row    power of two in [1, 64]: lanes of a wavefront that share one row
  *   chunks_per_lane  1..4: 16-byte chunks of one row each lane keeps in flight
+ *                    (with UD_TUNE_DEST_ALIGNED: 1, 2 or 4 output chunks per lane)
  *   rows_in_flight   1, 2 or 4: rows each lane group loads before storing any
  *                    (rows_in_flight x chunks_per_lane <= 8; 4 x 2 is not built)
  *   max_blocks       cap on workgroups (grid-stride beyond it).  A gather that should run beside another
@@ -192,24 +198,26 @@ typedef struct {
 } ud_tuning;
 
 enum {
-    UD_TUNE_NT_LOAD = 1u,       /* non-temporal (streaming) loads from the table */
-    UD_TUNE_NT_STORE = 2u,      /* non-temporal stores to out */
-    UD_TUNE_WAVE_PRIORITY = 8u, /* raise the gather wavefronts' issue priority (s_setprio): for gathers that
-                                   share the GPU with a compute kernel on another stream */
+    UD_TUNE_NT_STORE = 2u,      /* non-temporal (streaming) stores to out */
+    UD_TUNE_ELEMENTWISE = 4u,   /* one lane per element, rows straddling wavefronts: the layout of
+                                   the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
+                                   the comparison point and as the fallback for odd alignments */
     UD_TUNE_BIG_BLOCKS = 16u,   /* 1024-thread workgroups instead of 256: with a small max_blocks the whole
                                    gather then sits on few compute units and leaves the others, registers
                                    included, to a compute kernel running beside it */
     UD_TUNE_CIRCULAR_SHIFT = 32u, /* with UD_TUNE_ELEMENTWISE: rotate each row's lanes as in Section 4.5 / Figure 5 of
                                    the paper (its alignment fix), for comparison */
-    UD_TUNE_XCD_REMAP = 64u,    /* renumber workgroups so that each of the 8 XCDs (each with its own L2) serves one
-                                   contiguous range of output rows */
     UD_TUNE_SHARE_GPU = 128u,   /* launch shape for a gather that runs beside another stream's kernels: a grid of
                                    64 workgroups for rows of 1 KiB or more, 128 below (unless max_blocks is given),
                                    and enough rows in flight per lane group to keep about 1 KiB per wavefront on
                                    the link; 94-100% of the stand-alone rate */
-    UD_TUNE_ELEMENTWISE = 4u    /* one lane per element, rows straddling wavefronts: the layout of
-                                   the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
-                                   the comparison point and as the fallback for odd alignments */
+    UD_TUNE_DEST_ALIGNED = 256u /* the kernel that cuts the OUTPUT, taken as one dense stream, into aligned 16-byte
+                                   chunks (every store an aligned dwordx4, every output line written whole by one
+                                   wavefront) and reads the table with element-aligned loads.  The automatic
+                                   choice for tables in HBM, where the gather is bound by HBM bandwidth; tables
+                                   read over the host link use the source-aligned kernel (flag clear).  Uses
+                                   chunks_per_lane and max_blocks; lanes_per_row and rows_in_flight are ignored.
+                                   Not combinable with ELEMENTWISE, BIG_BLOCKS or SHARE_GPU */
 };
 
 /* ud_gather with explicit kernel parameters (for the tuning loop and for tests that
@@ -254,11 +262,17 @@ ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
 ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning *plan);
 
 /*
- * Waits for stream, then reports ID errors of gathers on the current device
- * since the previous ud_gather_status call: UD_OK and *bad_pos = -1 if none,
- * else UD_ERR_INDEX_OUT_OF_RANGE and *bad_pos = the smallest offending position
- * i (position in idx, not the ID).  bad_pos is written in both cases and may
- * be NULL.  The record is cleared.  It is shared by all streams of a device.
+ * Waits for stream, then reports the ID errors of the gathers and scatters that were enqueued on
+ * THAT stream (on the current device) since the previous ud_gather_status call for it: UD_OK and
+ * *bad_pos = -1 if none, else UD_ERR_INDEX_OUT_OF_RANGE and *bad_pos = the smallest offending
+ * position i (position in idx, not the ID).  bad_pos is written in both cases and may be NULL.
+ * The stream's record is read and cleared in one step, in stream order (a one-thread kernel on
+ * `stream`), so errors of work on other streams are neither reported nor lost, and nothing runs on
+ * the default stream.  Records are kept per stream for the first 63 streams that launch on a
+ * device; all further streams share one record.  A stream handle that is destroyed and handed out
+ * again by the runtime inherits its predecessor's record.  Gathers replayed from a HIP graph report
+ * to the record of the stream they were captured on: synchronise the replay, then query that stream.
+ * Not to be called while `stream` is being captured.
  */
 ud_status ud_gather_status(void *stream, int64_t *bad_pos);
 
@@ -266,6 +280,9 @@ ud_status ud_gather_status(void *stream, int64_t *bad_pos);
 const char *ud_status_str(ud_status s);
 /* HIP's message for the most recent UD_ERR_HIP / UD_ERR_OOM in this thread ("" if none). */
 const char *ud_last_hip_error(void);
+/* Identifies the sources this library was built from: the hex digest the build script computed over
+ * them ("unknown" for a build made some other way).  Static string. */
+const char *ud_build_id(void);
 
 #ifdef __cplusplus
 }

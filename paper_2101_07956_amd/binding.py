@@ -21,15 +21,15 @@ UD_OK, UD_ERR_INVALID_ARG, UD_ERR_UNSUPPORTED, UD_ERR_OOM, UD_ERR_INDEX_OUT_OF_R
 UD_F32, UD_F16, UD_F16_TO_F32 = 0, 1, 2
 UD_I64, UD_I32 = 0, 1
 UD_TABLE_COHERENT, UD_TABLE_NONCOHERENT, UD_TABLE_PAD_ROWS = 0, 1, 2
-UD_TUNE_NT_LOAD, UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE, UD_TUNE_WAVE_PRIORITY, UD_TUNE_BIG_BLOCKS = 1, 2, 4, 8, 16
-UD_TUNE_CIRCULAR_SHIFT, UD_TUNE_XCD_REMAP, UD_TUNE_SHARE_GPU = 32, 64, 128
+UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE, UD_TUNE_BIG_BLOCKS = 2, 4, 16
+UD_TUNE_CIRCULAR_SHIFT, UD_TUNE_SHARE_GPU, UD_TUNE_DEST_ALIGNED = 32, 128, 256
 
 #: every symbol include/ud.h declares
 EXPORTS = (
     "ud_alloc_table", "ud_table_to_device", "ud_table_host_ptr", "ud_table_device_ptr",
     "ud_table_shape", "ud_table_pitch", "ud_free_table", "ud_gather", "ud_gather_pitched", "ud_gather_tuned", "ud_gather_plan",
     "ud_gather_status", "ud_cache_create", "ud_cache_free", "ud_gather_cached",
-    "ud_scatter", "ud_scatter_tuned", "ud_scatter_pitched", "ud_status_str", "ud_last_hip_error",
+    "ud_scatter", "ud_scatter_tuned", "ud_scatter_pitched", "ud_status_str", "ud_last_hip_error", "ud_build_id",
 )
 
 
@@ -89,7 +89,9 @@ _lib.ud_status_str.argtypes = [_int]
 _lib.ud_status_str.restype = ctypes.c_char_p
 _lib.ud_last_hip_error.argtypes = []
 _lib.ud_last_hip_error.restype = ctypes.c_char_p
-for _n in EXPORTS[:-2]:
+_lib.ud_build_id.argtypes = []
+_lib.ud_build_id.restype = ctypes.c_char_p
+for _n in EXPORTS[:-3]:
     getattr(_lib, _n).restype = _int
 
 
@@ -105,6 +107,11 @@ def ud_status_str(status: int) -> str:
 
 def ud_last_hip_error() -> str:
     return _lib.ud_last_hip_error().decode()
+
+
+def ud_build_id() -> str:
+    """Digest of the sources the loaded library was built from."""
+    return _lib.ud_build_id().decode()
 
 
 def ud_alloc_table(N: int, D: int, elem: int, flags: int = UD_TABLE_COHERENT) -> int:

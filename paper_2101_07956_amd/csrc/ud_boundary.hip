@@ -10,6 +10,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "ud.h"
 #include "ud_internal.h"
@@ -53,36 +54,157 @@ bool mul3_overflows(int64_t a, int64_t b, int64_t c, int64_t *r)
     return __builtin_mul_overflow(a, b, &ab) || __builtin_mul_overflow(ab, c, r);
 }
 
-// One error word per device, allocated on the first gather and kept for the
-// life of the process.
+// ID-error records.  Every device has a small table of error slots in HBM, one
+// per stream that has launched a gather or scatter (the kernels take the slot's
+// address and atomic-min the position of a bad ID into it).  A stream keeps its
+// slot for the life of the process; the table is allocated once, on the first
+// launch on that device, and nothing is allocated per call.  The last slot is
+// shared by all streams beyond the first kErrSlots - 1.
 constexpr int kMaxDevices = 64;
-std::mutex g_err_mutex;
-unsigned long long *g_err_word[kMaxDevices] = {};
+constexpr int kErrSlots = 64;
 
-ud_status error_word(unsigned long long **w)
+struct SlotTable {
+    unsigned long long *words = nullptr;     // device memory, kErrSlots words
+    hipStream_t owner[kErrSlots] = {};
+    int used = 0;
+};
+
+struct DeviceState {
+    SlotTable heap;                          // hipMalloc'd at the first launch
+    unsigned long long *result_host = nullptr;   // pinned: where ud_gather_status receives a slot's value
+    unsigned long long *result_dev = nullptr;    // the same words as the GPU addresses them
+};
+
+std::mutex g_err_mutex;
+DeviceState g_dev[kMaxDevices];
+
+// Index of `stream`'s slot in t, claiming a free one if `claim`; -1 if it has none.
+int find_slot(SlotTable &t, hipStream_t stream, bool claim, bool share_last)
 {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    for (int k = 0; k < t.used; ++k)
+        if (t.owner[k] == stream)
+            return k;
+    if (t.used < kErrSlots - 1) {
+        if (!claim)
+            return -1;
+        t.owner[t.used] = stream;
+        return t.used++;
+    }
+    return share_last ? kErrSlots - 1 : -1;
+}
+
+ud_status current_device(int *dev)
+{
+    const hipError_t e = hipGetDevice(dev);
     if (e != hipSuccess)
         return hip_fail(e, "hipGetDevice");
-    if (dev < 0 || dev >= kMaxDevices)
+    if (*dev < 0 || *dev >= kMaxDevices)
         return UD_ERR_UNSUPPORTED;
+    return UD_OK;
+}
+
+// The error slot the kernels of a launch on `stream` report to.
+ud_status error_slot(hipStream_t stream, unsigned long long **w)
+{
+    // the common case: the same thread launching on the same stream again
+    thread_local int last_dev = -1;
+    thread_local hipStream_t last_stream = nullptr;
+    thread_local unsigned long long *last_slot = nullptr;
+    int dev = 0;
+    const ud_status st = current_device(&dev);
+    if (st != UD_OK)
+        return st;
+    if (last_slot && dev == last_dev && stream == last_stream) {
+        *w = last_slot;
+        return UD_OK;
+    }
     std::lock_guard<std::mutex> lock(g_err_mutex);
-    if (!g_err_word[dev]) {
+    SlotTable &t = g_dev[dev].heap;
+    if (!t.words) {
         unsigned long long *p = nullptr;
-        e = hipMalloc(reinterpret_cast<void **>(&p), sizeof *p);
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&p), kErrSlots * sizeof *p);
         if (e != hipSuccess)
-            return hip_fail(e, "hipMalloc(error word)");
-        const unsigned long long init = ud::kNoBadIndex;
-        e = hipMemcpy(p, &init, sizeof init, hipMemcpyHostToDevice);
+            return hip_fail(e, "hipMalloc(error slots)");
+        unsigned long long init[kErrSlots];
+        for (unsigned long long &x : init)
+            x = ud::kNoBadIndex;
+        e = hipMemcpy(p, init, sizeof init, hipMemcpyHostToDevice);
         if (e != hipSuccess) {
             (void)hipFree(p);
-            return hip_fail(e, "hipMemcpy(error word)");
+            return hip_fail(e, "hipMemcpy(error slots)");
         }
-        g_err_word[dev] = p;
+        t.words = p;
     }
-    *w = g_err_word[dev];
+    const int k = find_slot(t, stream, true, true);
+    *w = t.words + k;
+    if (k < kErrSlots - 1) {                 // the shared slot is not worth remembering
+        last_dev = dev;
+        last_stream = stream;
+        last_slot = *w;
+    }
     return UD_OK;
+}
+
+// Where a table lives decides the launch shape (the host link and HBM bound different kernels).
+// Tables made by this library are known exactly: their address ranges are kept here from
+// allocation to ud_free_table.
+struct Range {
+    uintptr_t lo, hi;
+    bool hbm;
+};
+std::mutex g_range_mutex;
+std::vector<Range> g_ranges;
+
+void remember_range(const void *p, size_t bytes, bool hbm)
+{
+    std::lock_guard<std::mutex> lock(g_range_mutex);
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+    g_ranges.push_back(Range{lo, lo + bytes, hbm});
+}
+
+void forget_range(const void *p)
+{
+    std::lock_guard<std::mutex> lock(g_range_mutex);
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+    for (size_t k = 0; k < g_ranges.size(); ++k)
+        if (g_ranges[k].lo == lo) {
+            g_ranges[k] = g_ranges.back();
+            g_ranges.pop_back();
+            return;
+        }
+}
+
+// A pointer inside no table of this library is asked of the runtime, and the answer kept in a
+// small per-thread cache (callers alternate between a few tables: a host table and its HBM
+// slice, say).  The cache is keyed on the address, so memory that is freed and allocated again as
+// the other kind can be misjudged until it leaves the cache; like an unknown pointer, which is
+// taken for host memory, that only costs launch-shape tuning, never correctness.
+bool table_is_in_hbm(const void *table)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(table);
+    {
+        std::lock_guard<std::mutex> lock(g_range_mutex);
+        for (const Range &r : g_ranges)
+            if (a >= r.lo && a < r.hi)
+                return r.hbm;
+    }
+    constexpr int kRecent = 8;
+    thread_local uintptr_t ptr[kRecent] = {};
+    thread_local bool kind[kRecent] = {};
+    thread_local int next = 0;
+    for (int k = 0; k < kRecent; ++k)
+        if (a && ptr[k] == a)
+            return kind[k];
+    hipPointerAttribute_t attr{};
+    bool in_hbm = false;
+    if (hipPointerGetAttributes(&attr, table) == hipSuccess)
+        in_hbm = attr.type == hipMemoryTypeDevice;
+    else
+        (void)hipGetLastError();
+    ptr[next] = a;
+    kind[next] = in_hbm;
+    next = (next + 1) % kRecent;
+    return in_hbm;
 }
 
 int next_pow2(int64_t x)
@@ -108,45 +230,27 @@ int64_t max_chunks_per_row(uintptr_t base, int64_t row_bytes, int64_t pitch_byte
 
 constexpr int kDefaultMaxBlocks = 1 << 22;
 
-// Where does the table live?  The two cases are bound by different things (the
-// host link, or HBM) and want different launch shapes.  Asked of the runtime
-// once per pointer and remembered per thread; an unknown pointer is treated as
-// host memory (this only steers tuning, never correctness).
-bool table_is_in_hbm(const void *table)
-{
-    thread_local const void *last_ptr = nullptr;
-    thread_local bool last_kind = false;
-    if (table && table == last_ptr)
-        return last_kind;
-    hipPointerAttribute_t attr{};
-    bool in_hbm = false;
-    if (hipPointerGetAttributes(&attr, table) == hipSuccess)
-        in_hbm = attr.type == hipMemoryTypeDevice;
-    else
-        (void)hipGetLastError();
-    last_ptr = table;
-    last_kind = in_hbm;
-    return in_hbm;
-}
-
 // Launch shape by row width and table residence, from sweeps on MI355X:
-//  * host table (link-bound): one row per wavefront instruction (64 lanes per
-//    row) for every row longer than 64 bytes, a single row in flight per lane
-//    group.  Whole-wave loads of one row reach 99-100% of the
-//    pinned-memcpy rate for 256..1024-byte rows; packing several short rows
-//    into one instruction costs 3-5%.  From 1 KiB rows up a fixed grid of 512
-//    workgroups striding over the rows is 1-3% faster than one wavefront per
-//    row; below that, one wavefront batch per workgroup slot is best.
-//  * HBM table (bandwidth-bound): no idle lanes (lanes per row = chunks per row
-//    rounded up to a power of two), two rows in flight, streaming stores.
-ud::Plan auto_plan(const void *table, int64_t D, int64_t pitch, ud_dtype dtype)
+//  * host table (link-bound): the source-aligned chunked kernel, one row per
+//    wavefront instruction (64 lanes per row) for every row longer than 64
+//    bytes, a single row in flight per lane group.  Whole-wave loads of one row
+//    reach 99-100% of the pinned-memcpy rate for 256..1024-byte rows; packing
+//    several short rows into one instruction costs 3-5%.  From 1 KiB rows up a
+//    fixed grid of 512 workgroups striding over the rows is 1-3% faster than
+//    one wavefront per row.
+//  * HBM table (bandwidth-bound): the destination-aligned kernel with streaming
+//    stores, kFlatChunks chunks per lane.
+constexpr int kFlatChunks = 4;
+
+// The source-aligned chunked kernel's shape (also the scatter's, which mirrors it).
+ud::Plan chunked_plan(const void *table, int64_t D, int64_t pitch, ud_dtype dtype, bool hbm)
 {
     const int64_t row_bytes = D * elem_bytes(dtype);
     const int64_t nch = max_chunks_per_row(reinterpret_cast<uintptr_t>(table), row_bytes, pitch * elem_bytes(dtype));
-    const bool hbm = table_is_in_hbm(table);
     ud::Plan p{};
     p.flags = hbm ? UD_TUNE_NT_STORE : 0u;
     p.max_blocks = kDefaultMaxBlocks;
+    p.tile_id_lines = !hbm;
     if (nch <= 64) {
         p.lanes_per_row = (!hbm && row_bytes > 64) ? 64 : next_pow2(nch);
         p.chunks_per_lane = 1;
@@ -160,6 +264,22 @@ ud::Plan auto_plan(const void *table, int64_t D, int64_t pitch, ud_dtype dtype)
     if (!hbm && row_bytes >= 1024)
         p.max_blocks = 512;
     return p;
+}
+
+// What ud_gather does by itself.
+ud::Plan auto_plan(const void *table, int64_t D, int64_t pitch, ud_dtype dtype)
+{
+    const bool hbm = table_is_in_hbm(table);
+    if (hbm) {
+        ud::Plan p{};
+        p.flags = UD_TUNE_NT_STORE | UD_TUNE_DEST_ALIGNED;
+        p.max_blocks = kDefaultMaxBlocks;
+        p.lanes_per_row = 64;              // not used by the destination-aligned kernel
+        p.chunks_per_lane = kFlatChunks;
+        p.rows_in_flight = 1;
+        return p;
+    }
+    return chunked_plan(table, D, pitch, dtype, hbm);
 }
 
 bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -224,6 +344,7 @@ ud_status ud_alloc_table(int64_t N, int64_t D, ud_dtype elem, unsigned flags, ud
         (void)hipHostFree(host);
         return UD_ERR_OOM;
     }
+    remember_range(dev, static_cast<size_t>(bytes), false);
     *t = h;
     return UD_OK;
 }
@@ -248,6 +369,7 @@ ud_status ud_table_to_device(const ud_table *src, int64_t row0, int64_t n, ud_ta
         (void)hipFree(dev);
         return UD_ERR_OOM;
     }
+    remember_range(dev, bytes, true);
     *t = h;
     return UD_OK;
 }
@@ -293,6 +415,7 @@ ud_status ud_free_table(ud_table *t)
 {
     if (!t)
         return UD_OK;
+    forget_range(t->dev);
     const hipError_t e = t->device_resident ? hipFree(t->dev) : hipHostFree(t->host);
     delete t;
     return e == hipSuccess ? UD_OK : hip_fail(e, "free");
@@ -333,10 +456,13 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pi
 
     ud::Plan plan = auto_plan(table, D, pitch, dtype);
     if (tuning) {
-        if (tuning->flags & ~(UD_TUNE_NT_LOAD | UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_WAVE_PRIORITY | UD_TUNE_BIG_BLOCKS |
-                              UD_TUNE_CIRCULAR_SHIFT | UD_TUNE_XCD_REMAP | UD_TUNE_SHARE_GPU))
+        if (tuning->flags & ~(UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_BIG_BLOCKS | UD_TUNE_CIRCULAR_SHIFT |
+                              UD_TUNE_SHARE_GPU | UD_TUNE_DEST_ALIGNED))
             return UD_ERR_INVALID_ARG;
         if ((tuning->flags & UD_TUNE_CIRCULAR_SHIFT) && !(tuning->flags & UD_TUNE_ELEMENTWISE))
+            return UD_ERR_INVALID_ARG;
+        if ((tuning->flags & UD_TUNE_DEST_ALIGNED) &&
+            (tuning->flags & (UD_TUNE_ELEMENTWISE | UD_TUNE_BIG_BLOCKS | UD_TUNE_SHARE_GPU)))
             return UD_ERR_INVALID_ARG;
         if (tuning->lanes_per_row < 0 || tuning->lanes_per_row > 64 ||
             (tuning->lanes_per_row && !is_pow2(tuning->lanes_per_row)))
@@ -348,6 +474,15 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pi
             return UD_ERR_INVALID_ARG;
         if (tuning->max_blocks < 0)
             return UD_ERR_INVALID_ARG;
+        if ((plan.flags & UD_TUNE_DEST_ALIGNED) && !(tuning->flags & UD_TUNE_DEST_ALIGNED)) {
+            // the automatic plan chose the destination-aligned kernel, the caller another one: start
+            // from the chunked kernel's defaults for this width
+            plan = chunked_plan(table, D, pitch, dtype, true);
+        } else if (!(plan.flags & UD_TUNE_DEST_ALIGNED) && (tuning->flags & UD_TUNE_DEST_ALIGNED)) {
+            plan.chunks_per_lane = kFlatChunks;
+            plan.rows_in_flight = 1;
+            plan.max_blocks = kDefaultMaxBlocks;
+        }
         plan.flags = tuning->flags;
         if (tuning->lanes_per_row)
             plan.lanes_per_row = tuning->lanes_per_row;
@@ -372,9 +507,17 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pi
                 plan.rows_in_flight = per_pass >= 1024 ? 1 : per_pass >= 512 ? 2 : 4;
             }
         }
-        if (plan.rows_in_flight * plan.chunks_per_lane > 8 || (plan.rows_in_flight == 4 && plan.chunks_per_lane == 2))
+        if (plan.flags & UD_TUNE_DEST_ALIGNED) {
+            if (!ud::flat_supports(N, D, pitch * elem_bytes(dtype), M) || plan.chunks_per_lane == 3)
+                return UD_ERR_UNSUPPORTED;
+        } else if (plan.rows_in_flight * plan.chunks_per_lane > 8 || (plan.rows_in_flight == 4 && plan.chunks_per_lane == 2)) {
             return UD_ERR_UNSUPPORTED;
+        }
     }
+
+    // the automatic choice falls back to the source-aligned kernel for shapes the other does not cover
+    if ((plan.flags & UD_TUNE_DEST_ALIGNED) && !ud::flat_supports(N, D, pitch * elem_bytes(dtype), M))
+        plan = chunked_plan(table, D, pitch, dtype, true);
 
     if (M == 0)
         return UD_OK;
@@ -395,16 +538,17 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pi
     a.out = out;
     a.slot = slot;
     a.cache = cache;
-    a.high_priority = (plan.flags & UD_TUNE_WAVE_PRIORITY) ? 1 : 0;
-    a.xcd_remap = (plan.flags & UD_TUNE_XCD_REMAP) ? 1 : 0;
-    const ud_status es = error_word(&a.err);
+    a.group_iters = 1;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const ud_status es = error_slot(s, &a.err);
     if (es != UD_OK)
         return es;
 
-    hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (plan.flags & UD_TUNE_ELEMENTWISE)
         e = ud::launch_elementwise(a, dtype, plan, s);
+    else if (plan.flags & UD_TUNE_DEST_ALIGNED)
+        e = ud::launch_flat(a, dtype, plan, s);
     else if (dtype == UD_F32)
         e = ud::launch_chunked_f32(a, plan, s);
     else if (dtype == UD_F16)
@@ -454,7 +598,7 @@ static ud_status scatter_impl(void *table, int64_t N, int64_t D, int64_t pitch, 
         return UD_ERR_INVALID_ARG;
     if (table_bytes > INT64_MAX - 64)
         return UD_ERR_INVALID_ARG;
-    ud::Plan plan = auto_plan(table, D, pitch, dtype);
+    ud::Plan plan = chunked_plan(table, D, pitch, dtype, table_is_in_hbm(table));
     plan.flags = 0;
     if (tuning) {
         if (tuning->flags)
@@ -492,7 +636,8 @@ static ud_status scatter_impl(void *table, int64_t N, int64_t D, int64_t pitch, 
     a.M = M;
     a.out = const_cast<void *>(src);
     a.pitch_bytes = pitch * elem_bytes(dtype);
-    const ud_status es = error_word(&a.err);
+    a.group_iters = 1;
+    const ud_status es = error_slot(static_cast<hipStream_t>(stream), &a.err);
     if (es != UD_OK)
         return es;
     const hipError_t e = ud::launch_scatter(a, elem_bytes(dtype), plan, static_cast<hipStream_t>(stream));
@@ -605,31 +750,53 @@ ud_status ud_gather_status(void *stream, int64_t *bad_pos)
 {
     if (bad_pos)
         *bad_pos = -1;
-    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
-    if (e != hipSuccess)
-        return hip_fail(e, "hipStreamSynchronize");
+    hipStream_t s = static_cast<hipStream_t>(stream);
     int dev = 0;
-    e = hipGetDevice(&dev);
-    if (e != hipSuccess)
-        return hip_fail(e, "hipGetDevice");
-    unsigned long long *w = nullptr;
+    ud_status st = current_device(&dev);
+    if (st != UD_OK)
+        return st;
+    unsigned long long *slot = nullptr, *res_host = nullptr, *res_dev = nullptr;
     {
         std::lock_guard<std::mutex> lock(g_err_mutex);
-        if (dev >= 0 && dev < kMaxDevices)
-            w = g_err_word[dev];
+        DeviceState &d = g_dev[dev];
+        const int k = d.heap.words ? find_slot(d.heap, s, false, true) : -1;
+        if (k >= 0) {
+            if (!d.result_host) {
+                // one pinned word per slot, so that status calls on different streams do not share one
+                void *h = nullptr, *g = nullptr;
+                hipError_t e = hipHostMalloc(&h, kErrSlots * sizeof(unsigned long long), hipHostMallocMapped | hipHostMallocCoherent);
+                if (e == hipSuccess) {
+                    e = hipHostGetDevicePointer(&g, h, 0);
+                    if (e != hipSuccess)
+                        (void)hipHostFree(h);
+                }
+                if (e != hipSuccess)
+                    return hip_fail(e, "hipHostMalloc(status words)");
+                d.result_host = static_cast<unsigned long long *>(h);
+                d.result_dev = static_cast<unsigned long long *>(g);
+            }
+            slot = d.heap.words + k;
+            res_host = d.result_host + k;
+            res_dev = d.result_dev + k;
+        }
     }
-    if (!w)
-        return UD_OK; // no gather has run on this device yet
-    unsigned long long v = ud::kNoBadIndex;
-    e = hipMemcpy(&v, w, sizeof v, hipMemcpyDeviceToHost);
+    hipError_t e;
+    if (slot) {
+        // read and clear in one atomic step, ordered after this stream's gathers and before its next ones;
+        // other streams' slots are not touched
+        *res_host = ud::kNoBadIndex;
+        e = ud::launch_fetch_and_reset(slot, res_dev, s);
+        if (e != hipSuccess)
+            return hip_fail(e, "status kernel launch");
+    }
+    e = hipStreamSynchronize(s);
     if (e != hipSuccess)
-        return hip_fail(e, "hipMemcpy(error word)");
+        return hip_fail(e, "hipStreamSynchronize");
+    if (!slot)
+        return UD_OK;                       // nothing was ever launched on this stream
+    const unsigned long long v = *static_cast<volatile unsigned long long *>(res_host);
     if (v == ud::kNoBadIndex)
         return UD_OK;
-    const unsigned long long init = ud::kNoBadIndex;
-    e = hipMemcpy(w, &init, sizeof init, hipMemcpyHostToDevice);
-    if (e != hipSuccess)
-        return hip_fail(e, "hipMemcpy(error word reset)");
     if (bad_pos)
         *bad_pos = static_cast<int64_t>(v);
     return UD_ERR_INDEX_OUT_OF_RANGE;
@@ -649,5 +816,10 @@ const char *ud_status_str(ud_status s)
 }
 
 const char *ud_last_hip_error(void) { return g_hip_msg; }
+
+#ifndef UD_BUILD_ID
+#define UD_BUILD_ID "unknown"
+#endif
+const char *ud_build_id(void) { return UD_BUILD_ID; }
 
 } // extern "C"

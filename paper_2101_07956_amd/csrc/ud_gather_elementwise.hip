@@ -69,6 +69,34 @@ hipError_t launch_fill_slots(const int64_t *rows, int64_t n, int32_t *slot, hipS
     return hipGetLastError();
 }
 
+// *result = old value of *slot, and *slot = "no bad ID", in one atomic step.  `result` is pinned host
+// memory the GPU can write.
+__global__ void fetch_and_reset(unsigned long long *slot, unsigned long long *result)
+{
+    *result = atomicExch(slot, kNoBadIndex);
+}
+
+hipError_t launch_fetch_and_reset(unsigned long long *slot, unsigned long long *result, hipStream_t s)
+{
+    hipLaunchKernelGGL(fetch_and_reset, dim3(1), dim3(1), 0, s, slot, result);
+    return hipGetLastError();
+}
+
+__global__ void init_slots(unsigned long long *words, int n)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < n)
+        words[k] = kNoBadIndex;
+}
+
+hipError_t launch_init_slots(unsigned long long *words, int n, hipStream_t s)
+{
+    if (n < 1)
+        return hipSuccess;
+    hipLaunchKernelGGL(init_slots, dim3((n + 63) / 64), dim3(64), 0, s, words, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_elementwise(const GatherArgs &a, int dtype, const Plan &p, hipStream_t s)
 {
     const int64_t total = a.M * a.D;

@@ -39,6 +39,9 @@ namespace ud {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // same vector, only dword-aligned
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));   // same vector, only 2-byte aligned
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x2 u32x2_a2 __attribute__((aligned(2)));
 
 // Every pointer this library dereferences on the GPU is a global-memory
 // address (HBM or GPU-mapped host memory), never LDS or scratch; saying so lets
@@ -46,14 +49,9 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));   // same vector, only dword
 #define UD_GLOBAL __attribute__((address_space(1)))
 
 // 16-byte aligned 16-byte load from the table
-template <bool NT>
 __device__ __forceinline__ u32x4 ld_chunk(const char *p)
 {
-    const UD_GLOBAL u32x4 *g = (const UD_GLOBAL u32x4 *)p;
-    if constexpr (NT)
-        return __builtin_nontemporal_load(g);
-    else
-        return *g;
+    return *(const UD_GLOBAL u32x4 *)p;
 }
 
 // 16-byte store that is only dword-aligned
@@ -148,13 +146,19 @@ __device__ __forceinline__ void store_halves(uint16_t *d, u32x4 v, int lo, int h
 // Workgroups are 256 threads by default and 1024 on request (all waves of a
 // workgroup share a compute unit, so few large workgroups keep the gather on few
 // compute units): the launch bound is the larger of the two.
-template <int DT, int U, int P, bool NTL, bool NTS>
+//
+// Row order: one pass of a workgroup covers waves x rows-per-wave consecutive
+// output rows, and a workgroup makes group_iters passes over adjacent rows
+// before it strides on by the grid.  For host-resident tables the host sizes
+// group_iters so that these rows span at least one 128-byte line of the ID
+// list: the line is then fetched from HBM by one XCD's L2 once, instead of by
+// every XCD whose workgroups happen to hold a few of its IDs.  (For HBM-resident
+// tables group_iters is 1: there, several passes per wavefront cost up to 12%.)
+template <int DT, int U, int P, bool NTS>
 __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a, int lg)
 {
     constexpr int IN_ESZ = (DT == UD_F32) ? 4 : 2;      // table element bytes
     constexpr int EPC = 16 / IN_ESZ;                    // elements per 16-byte chunk
-    if (a.high_priority)
-        __builtin_amdgcn_s_setprio(3);                  // issue ahead of a co-running compute kernel's waves
     const int lane = threadIdx.x & 63;
     const int lpr = 1 << lg;
     const int grp = lane >> lg;                         // which row of the wavefront's batch
@@ -162,38 +166,43 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
     const int rpw = 64 >> lg;                           // rows per wavefront per pass
     const int64_t rows_per_iter = static_cast<int64_t>(rpw) * U;
     const int waves_per_block = blockDim.x >> 6;
-    // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  With the
-    // remap each XCD serves one contiguous eighth of the output rows, so that neighbouring rows --
-    // which share ID-list lines and, for widths that are no multiple of 128 bytes, output lines --
-    // meet in the same L2.  The host rounds the grid up to a multiple of 8 for this.
-    int64_t block = blockIdx.x;
-    if (a.xcd_remap)
-        block = static_cast<int64_t>(blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int64_t wave = block * waves_per_block + (threadIdx.x >> 6);
-    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * waves_per_block;
+    const int64_t rows_per_pass = rows_per_iter * waves_per_block;     // rows one workgroup pass covers
+    const int64_t rows_per_tile = rows_per_pass * a.group_iters;
+    const int64_t wave_first = static_cast<int64_t>(threadIdx.x >> 6) * rows_per_iter;
     const int64_t row_bytes = a.D * IN_ESZ;
     // upper bound of chunks per row over all alignments; identical in every lane
     const int64_t span = static_cast<int64_t>(P) * lpr;
     const int64_t nch_bound = (row_bytes + 15 + 15) >> 4;
 
-    for (int64_t rb = wave * rows_per_iter; rb < a.M; rb += nwaves * rows_per_iter) {
-        int64_t i[U];
+    for (int64_t tile = static_cast<int64_t>(blockIdx.x) * rows_per_tile; tile < a.M;
+         tile += static_cast<int64_t>(gridDim.x) * rows_per_tile)
+    for (int g = 0; g < a.group_iters; ++g) {
+        const int64_t rb = tile + g * rows_per_pass + wave_first;
+        if (rb >= a.M)
+            break;
+        int64_t i[U], r[U];
         const char *base[U]; // 16-byte aligned address at or below the row's first byte
         int head[U];         // bytes between base and the row's first byte
         int64_t nch[U];      // chunks the row overlaps; 0 = nothing to do
+        // all ID loads first, then their uses: one round trip for the U rows, not U
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             i[u] = rb + static_cast<int64_t>(u) * rpw + grp;
+            r[u] = 0;
+            if (i[u] < a.M)
+                r[u] = load_id(a.idx, a.itype, i[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
             nch[u] = 0;
             base[u] = a.table;
             head[u] = 0;
             if (i[u] < a.M) {
-                const int64_t r = load_id(a.idx, a.itype, i[u]);
-                if (r < 0 || r >= a.N) {
+                if (r[u] < 0 || r[u] >= a.N) {
                     if (l == 0)
                         atomicMin(a.err, static_cast<unsigned long long>(i[u]));
                 } else {
-                    const char *src = row_source(a, r, row_bytes);
+                    const char *src = row_source(a, r[u], row_bytes);
                     head[u] = static_cast<int>(reinterpret_cast<uintptr_t>(src) & 15u);
                     base[u] = src - head[u];
                     nch[u] = (head[u] + row_bytes + 15) >> 4;
@@ -210,7 +219,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
                     const int64_t c = cb + static_cast<int64_t>(p) * lpr + l;
                     v[u][p] = u32x4{0, 0, 0, 0};
                     if (c < nch[u])
-                        v[u][p] = ld_chunk<NTL>(base[u] + c * 16);
+                        v[u][p] = ld_chunk(base[u] + c * 16);
                 }
             }
 #pragma unroll
@@ -250,37 +259,33 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
 template <int DT, int U, int P>
 hipError_t launch_nt(const GatherArgs &a, const Plan &p, int lg, dim3 grid, dim3 block, hipStream_t s)
 {
-    const bool ntl = p.flags & UD_TUNE_NT_LOAD, nts = p.flags & UD_TUNE_NT_STORE;
-    if (ntl && nts)
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, true>), grid, block, 0, s, a, lg);
-    else if (ntl)
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, false>), grid, block, 0, s, a, lg);
-    else if (nts)
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, true>), grid, block, 0, s, a, lg);
+    if (p.flags & UD_TUNE_NT_STORE)
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, true>), grid, block, 0, s, a, lg);
     else
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, false>), grid, block, 0, s, a, lg);
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, false>), grid, block, 0, s, a, lg);
     return hipGetLastError();
 }
 
-// Host side: pick the (U, P) instantiation and the grid.
+// Host side: pick the (U, P) instantiation, the row tiling and the grid.
 template <int DT>
-hipError_t launch_chunked(const GatherArgs &a, const Plan &p, hipStream_t s)
+hipError_t launch_chunked(const GatherArgs &a_in, const Plan &p, hipStream_t s)
 {
     int lg = 0;
     while ((1 << lg) < p.lanes_per_row)
         ++lg;
     if ((1 << lg) != p.lanes_per_row || lg > 6)
         return hipErrorInvalidValue;
-    const int64_t rows_per_wave = static_cast<int64_t>(64 >> lg) * p.rows_in_flight;
-    const int64_t waves = (a.M + rows_per_wave - 1) / rows_per_wave;
+    GatherArgs a = a_in;
     const int wpb = (p.flags & UD_TUNE_BIG_BLOCKS) ? kMaxBlockThreads / 64 : kWavesPerBlock;
-    int64_t blocks = (waves + wpb - 1) / wpb;
+    const int64_t rows_per_pass = static_cast<int64_t>(64 >> lg) * p.rows_in_flight * wpb;
+    const int64_t ids_per_line = a.itype == UD_I64 ? 16 : 32;         // IDs in a 128-byte line of the list
+    a.group_iters = p.tile_id_lines ? static_cast<int>((ids_per_line + rows_per_pass - 1) / rows_per_pass) : 1;
+    const int64_t rows_per_tile = rows_per_pass * a.group_iters;
+    int64_t blocks = (a.M + rows_per_tile - 1) / rows_per_tile;
     if (blocks > p.max_blocks)
         blocks = p.max_blocks;
     if (blocks < 1)
         return hipSuccess;
-    if (a.xcd_remap)
-        blocks = (blocks + 7) & ~static_cast<int64_t>(7);      // surplus wavefronts find no rows and exit
     const dim3 grid(static_cast<unsigned>(blocks)), block(static_cast<unsigned>(wpb * 64));
     const int key = p.rows_in_flight * 10 + p.chunks_per_lane;
     switch (key) {

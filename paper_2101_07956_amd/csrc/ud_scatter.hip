@@ -7,9 +7,11 @@
 // 16-byte chunks of memory it overlaps, aligned on the DESTINATION (table)
 // address, so that every full chunk is one aligned dwordx4 store and a
 // wavefront store instruction covers consecutive whole lines of the table.
-// Unlike a load, a store must not spill over the row's ends: the partial head
-// and tail chunks are written element by element.  The source rows (dense, in
-// HBM) generally have another alignment and are read with dword-aligned loads.
+// Unlike a load, a store must not spill over the row's ends: of the partial head
+// and tail chunks only the row's own elements are loaded (element by element,
+// in the same load phase as the full chunks, so that nothing waits on them
+// alone) and stored.  The source rows (dense, in HBM) generally have another
+// alignment and are read with loads that are only element-aligned.
 #include "ud_gather_kernel.hpp"
 
 namespace ud {
@@ -18,19 +20,29 @@ namespace ud {
 template <int ESZ>
 __device__ __forceinline__ u32x4 ld_src_chunk(const char *p)
 {
-    if constexpr (ESZ == 4) {
+    if constexpr (ESZ == 4)
         return *(const UD_GLOBAL u32x4_a4 *)p;
+    else
+        return *(const UD_GLOBAL u32x4_a2 *)p;
+}
+
+// Elements [lo, hi) of the 16 bytes at p (the others read as zero and are never stored).
+template <int ESZ>
+__device__ __forceinline__ u32x4 ld_src_partial(const char *p, int lo, int hi)
+{
+    uint32_t w[4] = {0, 0, 0, 0};
+    if constexpr (ESZ == 4) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (q >= lo && q < hi)
+                w[q] = ((const UD_GLOBAL uint32_t *)p)[q];
     } else {
-        if ((reinterpret_cast<uintptr_t>(p) & 3u) == 0)
-            return *(const UD_GLOBAL u32x4_a4 *)p;
-        const UD_GLOBAL uint16_t *h = (const UD_GLOBAL uint16_t *)p;
-        u32x4 v;
-        v.x = h[0] | (static_cast<uint32_t>(h[1]) << 16);
-        v.y = h[2] | (static_cast<uint32_t>(h[3]) << 16);
-        v.z = h[4] | (static_cast<uint32_t>(h[5]) << 16);
-        v.w = h[6] | (static_cast<uint32_t>(h[7]) << 16);
-        return v;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (q >= lo && q < hi)
+                w[q >> 1] |= static_cast<uint32_t>(((const UD_GLOBAL uint16_t *)p)[q]) << ((q & 1) * 16);
     }
+    return u32x4{w[0], w[1], w[2], w[3]};
 }
 
 // ESZ: element bytes (4 or 2).  U rows in flight per lane group, P chunks per
@@ -80,42 +92,48 @@ __global__ __launch_bounds__(kBlockThreads) void scatter_chunked(GatherArgs a, i
         }
         for (int64_t cb = 0; cb < nch_bound; cb += span) {
             u32x4 v[U][P];
-            bool full[U][P];
+            int lo[U][P], hi[U][P];      // elements of the chunk that belong to the row; lo >= hi: no chunk
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
                     const int64_t c = cb + static_cast<int64_t>(p) * lpr + l;
-                    const int64_t e0 = c * EPC - head[u] / ESZ;
-                    full[u][p] = c < nch[u] && e0 >= 0 && e0 + EPC <= a.D;
+                    const int64_t e0 = c * EPC - head[u] / ESZ;   // first element of the chunk, relative to the row
+                    const int64_t left = a.D - e0;
+                    lo[u][p] = e0 < 0 ? static_cast<int>(-e0) : 0;
+                    hi[u][p] = c < nch[u] ? (left < EPC ? static_cast<int>(left) : EPC) : 0;
                     v[u][p] = u32x4{0, 0, 0, 0};
-                    if (full[u][p])
-                        v[u][p] = ld_src_chunk<ESZ>(src + (i[u] * a.D + e0) * ESZ);
+                    const char *s16 = src + (i[u] * a.D + e0) * ESZ;
+                    if (lo[u][p] == 0 && hi[u][p] == EPC)
+                        v[u][p] = ld_src_chunk<ESZ>(s16);
+                    else if (lo[u][p] < hi[u][p])
+                        v[u][p] = ld_src_partial<ESZ>(s16, lo[u][p], hi[u][p]);
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
-                    const int64_t c = cb + static_cast<int64_t>(p) * lpr + l;
-                    if (c >= nch[u])
+                    if (lo[u][p] >= hi[u][p])
                         continue;
-                    if (full[u][p]) {
-                        *(UD_GLOBAL u32x4 *)(base[u] + c * 16) = v[u][p];
+                    const int64_t c = cb + static_cast<int64_t>(p) * lpr + l;
+                    char *d16 = base[u] + c * 16;
+                    if (lo[u][p] == 0 && hi[u][p] == EPC) {
+                        *(UD_GLOBAL u32x4 *)d16 = v[u][p];
                         continue;
                     }
                     // head or tail chunk: only the elements that belong to the row
-                    const int64_t e0 = c * EPC - head[u] / ESZ;
-                    const int lo = e0 < 0 ? static_cast<int>(-e0) : 0;
-                    const int64_t left = a.D - e0;
-                    const int hi = left < EPC ? static_cast<int>(left) : EPC;
-                    for (int q = lo; q < hi; ++q) {
-                        if constexpr (ESZ == 4)
-                            ((UD_GLOBAL uint32_t *)(base[u] + c * 16))[q] =
-                                ((const UD_GLOBAL uint32_t *)src)[i[u] * a.D + e0 + q];
-                        else
-                            ((UD_GLOBAL uint16_t *)(base[u] + c * 16))[q] =
-                                ((const UD_GLOBAL uint16_t *)src)[i[u] * a.D + e0 + q];
+                    const uint32_t w[4] = {v[u][p].x, v[u][p].y, v[u][p].z, v[u][p].w};
+                    if constexpr (ESZ == 4) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (q >= lo[u][p] && q < hi[u][p])
+                                ((UD_GLOBAL uint32_t *)d16)[q] = w[q];
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q)
+                            if (q >= lo[u][p] && q < hi[u][p])
+                                ((UD_GLOBAL uint16_t *)d16)[q] = static_cast<uint16_t>(w[q >> 1] >> ((q & 1) * 16));
                     }
                 }
             }

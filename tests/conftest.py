@@ -14,13 +14,11 @@ def pytest_configure(config):
 
 
 def _build_if_nothing_is_built():
-    """The tests load the in-tree libraries as built; only a tree with no library at all is built first
-    (hipcc cross-compiles without a GPU).  After changing a source, rebuild before running the tests."""
-    pkg = os.path.join(ROOT, "paper_2101_07956_amd")
-    if all(os.path.exists(os.path.join(pkg, lib)) for lib in ("libud.so", "libud_baseline.so")):
-        return
+    """The tests load the in-tree libraries as built.  A tree with no library, or with libraries whose build
+    stamp does not match the sources as they are now (an edit since the last build), is built first: hipcc
+    cross-compiles without a GPU, and a parity run must belong to the code in the tree."""
     from paper_2101_07956_amd import build as hip_build
-    hip_build.build(verbose=False)
+    hip_build.ensure_built(verbose=False)
 
 
 def pytest_collection_modifyitems(config, items):

@@ -83,12 +83,20 @@ def test_tuning_fields_are_range_checked(ud):
     assert _gather(ud, tuning=T(0, 5, 0, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 3, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, -1, 0)) == inv
-    assert _gather(ud, tuning=T(0, 0, 0, 0, 256)) == inv
+    assert _gather(ud, tuning=T(0, 0, 0, 0, 512)) == inv      # unknown flag
+    for gone in (1, 8, 64):                                   # options earlier versions had: no longer accepted
+        assert _gather(ud, tuning=T(0, 0, 0, 0, gone)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, 0, 32)) == inv       # circular shift needs the one-lane-per-element kernel
+    DA = ud.UD_TUNE_DEST_ALIGNED
+    for other in (ud.UD_TUNE_ELEMENTWISE, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_SHARE_GPU):
+        assert _gather(ud, tuning=T(0, 0, 0, 0, DA | other)) == inv
+    assert _gather(ud, tuning=T(0, 3, 0, 0, DA)) == ud.UD_ERR_UNSUPPORTED     # 1, 2 or 4 output chunks per lane
+    assert _gather(ud, M=0, tuning=T(0, 4, 0, 0, DA | ud.UD_TUNE_NT_STORE)) == ud.UD_OK
+    assert _gather(ud, M=0, D=2**31, N=1, tuning=T(0, 1, 0, 0, DA)) == ud.UD_ERR_UNSUPPORTED   # columns are 32-bit there
     assert _gather(ud, tuning=T(0, 0, 8, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 4, 4, 0, 0)) == ud.UD_ERR_UNSUPPORTED   # no such instantiation
     assert _gather(ud, tuning=T(0, 2, 4, 0, 0)) == ud.UD_ERR_UNSUPPORTED
-    assert _gather(ud, M=0, tuning=T(64, 2, 2, 0, 3)) == ud.UD_OK
+    assert _gather(ud, M=0, tuning=T(64, 2, 2, 0, 2)) == ud.UD_OK
 
 
 def test_table_calls_reject_bad_arguments(ud):
@@ -126,6 +134,13 @@ def test_plan_follows_row_width(ud):
     # rows that start at 4 different offsets modulo 16 can overlap one more chunk
     p = ud.ud_gather_plan(0x10000, 255, ud.UD_F32)      # 1020-byte rows: up to 65 chunks
     assert (p.lanes_per_row, p.chunks_per_lane) == (64, 2)
+
+
+def test_build_stamp_matches_the_sources(ud):
+    # the library says which sources it was built from; the build module recognises a stale one
+    from paper_2101_07956_amd import build
+    assert not build.stale()
+    assert ud.ud_build_id() == build.source_digest()
 
 
 def test_header_is_plain_c_and_the_library_links_from_c(ud, tmp_path):

@@ -71,8 +71,8 @@ def test_config1_single_gather(ud):
     t.free()
 
 
-WIDTHS = [1, 2, 3, 4, 5, 7, 16, 25, 64, 100, 127, 128, 129, 255, 256, 257, 300, 512, 513, 515, 518, 519, 602, 603,
-          1031, 4096, 4099]
+WIDTHS = [1, 2, 3, 4, 5, 7, 16, 25, 64, 100, 127, 128, 129, 255, 256, 257, 300, 512, 513, 514, 515, 516, 517, 518, 519,
+          602, 603, 1031, 4096, 4099]          # 512..519 are the row sizes 2048..2076 bytes of the paper's Figure 7
 
 
 @pytest.mark.parametrize("D", WIDTHS)
@@ -106,7 +106,7 @@ PLANS = [(u, p) for u, p in itertools.product((1, 2, 4), (1, 2, 3, 4)) if u * p 
 @pytest.mark.parametrize("u,p", PLANS)
 def test_every_instantiation_every_group_size(ud, u, p):
     # each (rows in flight, chunks per lane) kernel with each lane-group size, with and
-    # without streaming hints, on a width whose rows start at 4 different offsets mod 16
+    # without streaming stores, on a width whose rows start at 4 different offsets mod 16
     N, M = 1201, 1103
     cases = [(ud.UD_F32, ud.UD_F32, 77), (ud.UD_F16, ud.UD_F16_TO_F32, 301), (ud.UD_F16, ud.UD_F16, 75)]
     for elem, dtype, D in cases:
@@ -114,8 +114,7 @@ def test_every_instantiation_every_group_size(ud, u, p):
         idx = workloads.indices_uniform(9, M, N)
         want = oracle_bits(t.numpy(), idx, dtype)
         for lanes in (1, 2, 4, 8, 16, 32, 64):
-            for flags in (0, ud.UD_TUNE_NT_LOAD | ud.UD_TUNE_NT_STORE, ud.UD_TUNE_BIG_BLOCKS | ud.UD_TUNE_WAVE_PRIORITY,
-                          ud.UD_TUNE_XCD_REMAP):
+            for flags in (0, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_BIG_BLOCKS):
                 tun = ud.ud_tuning(lanes, p, u, 0, flags)
                 got = run_gather(ud, t, idx, dtype, tun)
                 assert np.array_equal(got, want), (dtype, D, lanes, u, p, flags)
@@ -128,7 +127,7 @@ def test_grid_stride_when_blocks_are_capped(ud):
     idx = workloads.indices_uniform(10, M, N)
     want = oracle_bits(t.numpy(), idx, oracle.F32)
     for blocks in (1, 7, 256):
-        for flags in (0, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_XCD_REMAP):
+        for flags in (0, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_DEST_ALIGNED, ud.UD_TUNE_DEST_ALIGNED | ud.UD_TUNE_NT_STORE):
             got = run_gather(ud, t, idx, ud.UD_F32, ud.ud_tuning(0, 0, 0, blocks, flags))
             assert np.array_equal(got, want), (blocks, flags)
     t.free()
@@ -150,13 +149,15 @@ def test_elementwise_kernel(ud, dtype_name, elem_name, D):
     t.free()
 
 
-@pytest.mark.parametrize("D", [1, 3, 11, 63, 64, 65, 100, 513, 602])
-def test_circular_shift_kernel_widths(ud, D):
+@pytest.mark.parametrize("D", [1, 3, 11, 63, 64, 65, 100, 512, 513, 514, 515, 516, 517, 518, 519, 602])
+def test_one_lane_per_element_and_circular_shift_kernel_widths(ud, D):
+    # the paper's two thread layouts (Figures 4 and 5), among others on all eight row sizes of its Figure 7
     N, M = 1501, 2203
     t = make_table(ud, N, D, ud.UD_F32, 700 + D)
     idx = workloads.indices_uniform(12, M, N)
-    got = run_gather(ud, t, idx, ud.UD_F32, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_ELEMENTWISE | ud.UD_TUNE_CIRCULAR_SHIFT))
-    assert np.array_equal(got, oracle_bits(t.numpy(), idx, oracle.F32)), D
+    want = oracle_bits(t.numpy(), idx, oracle.F32)
+    for flags in (ud.UD_TUNE_ELEMENTWISE, ud.UD_TUNE_ELEMENTWISE | ud.UD_TUNE_CIRCULAR_SHIFT):
+        assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32, ud.ud_tuning(0, 0, 0, 0, flags)), want), (D, flags)
     t.free()
 
 
@@ -319,7 +320,16 @@ def test_plan_depends_on_where_the_table_lives(ud):
     assert host_plan.lanes_per_row == 64 and host_plan.rows_in_flight == 1 and host_plan.flags == 0
     d = t.to_device()
     dev_plan = ud.ud_gather_plan(d.device_ptr, 128, ud.UD_F32)
-    assert dev_plan.lanes_per_row == 32 and dev_plan.rows_in_flight == 2 and dev_plan.flags == ud.UD_TUNE_NT_STORE
+    assert dev_plan.flags & ud.UD_TUNE_DEST_ALIGNED and dev_plan.chunks_per_lane in (1, 2, 4)
+    # a pointer into the middle of a table the library made is recognised too
+    mid_plan = ud.ud_gather_plan(d.device_ptr + 128 * 4 * 100, 128, ud.UD_F32)
+    assert mid_plan.flags == dev_plan.flags
+    # explicit tuning without the flag selects the source-aligned kernel on the same table
+    idx = workloads.indices_uniform(27, 3000, 5000)
+    want = oracle_bits(t.numpy(), idx, oracle.F32)
+    for tun in (ud.ud_tuning(0, 0, 0, 0, 0), ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_NT_STORE),
+                ud.ud_tuning(0, 0, 0, 0, dev_plan.flags), None):
+        assert np.array_equal(run_gather(ud, d, idx, ud.UD_F32, tun), want)
     d.free()
     t.free()
 
@@ -469,6 +479,75 @@ def test_two_streams_gather_concurrently(ud):
     t.free()
 
 
+def test_id_errors_are_recorded_per_stream(ud):
+    N, D, M = 20_000, 256, 200_000
+    t = make_table(ud, N, D, ud.UD_F32, 66)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    good = workloads.indices_uniform(67, M, N)
+    bad_a, bad_b = good.copy(), good.copy()
+    bad_a[777] = -5
+    bad_b[M - 3] = N
+    d_good, d_a, d_b = (torch.from_numpy(x).cuda() for x in (good, bad_a, bad_b))
+    outs = [torch.empty((M, D), dtype=torch.float32, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+
+    def launch(stream, ids, out):
+        ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, ids.data_ptr(), ud.UD_I64, M, out.data_ptr(), stream.cuda_stream)
+
+    # a bad ID on stream A only: B reports nothing, A reports its position, then A is clean again
+    launch(sa, d_a, outs[0])
+    launch(sb, d_good, outs[1])
+    ud.ud_gather_status(sb.cuda_stream)
+    with pytest.raises(ud.UdIndexError) as e:
+        ud.ud_gather_status(sa.cuda_stream)
+    assert e.value.pos == 777
+    ud.ud_gather_status(sa.cuda_stream)
+    assert np.array_equal(outs[1].cpu().numpy().view(np.uint32), oracle_bits(t.numpy(), good, oracle.F32))
+    # B's bad gather is in flight while A's record is read and cleared: B's error is not lost
+    launch(sa, d_a, outs[0])
+    for _ in range(3):
+        launch(sb, d_good, outs[1])
+    launch(sb, d_b, outs[1])
+    with pytest.raises(ud.UdIndexError) as e:
+        ud.ud_gather_status(sa.cuda_stream)
+    assert e.value.pos == 777
+    ud.ud_gather_status(sa.cuda_stream)
+    with pytest.raises(ud.UdIndexError) as e:
+        ud.ud_gather_status(sb.cuda_stream)
+    assert e.value.pos == M - 3
+    for st in (sa, sb):
+        ud.ud_gather_status(st.cuda_stream)
+    # a stream that never launched anything has nothing to report
+    ud.ud_gather_status(torch.cuda.Stream().cuda_stream)
+    t.free()
+
+
+def test_more_streams_than_error_slots(ud):
+    # streams beyond the per-device slot table share one record; results and reports stay correct
+    N, D, M = 2000, 64, 1500
+    t = make_table(ud, N, D, ud.UD_F32, 68)
+    idx = workloads.indices_uniform(69, M, N)
+    want = oracle_bits(t.numpy(), idx, oracle.F32)
+    didx = torch.from_numpy(idx).cuda()
+    bad = idx.copy()
+    bad[5] = N
+    dbad = torch.from_numpy(bad).cuda()
+    out = torch.empty((M, D), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(70)]
+    for st in streams:
+        ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, out.data_ptr(), st.cuda_stream)
+        ud.ud_gather_status(st.cuda_stream)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), want)
+    last = streams[-1]
+    ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, dbad.data_ptr(), ud.UD_I64, M, out.data_ptr(), last.cuda_stream)
+    with pytest.raises(ud.UdIndexError) as e:
+        ud.ud_gather_status(last.cuda_stream)
+    assert e.value.pos == 5
+    ud.ud_gather_status(last.cuda_stream)
+    t.free()
+
+
 def test_gathers_captured_in_a_hip_graph_replay_correctly(ud):
     # a launch-bound inner loop (several small gathers) captured once and replayed with new IDs each time;
     # the first eager call is what allocates the library's error word, so it runs before capture
@@ -493,26 +572,91 @@ def test_gathers_captured_in_a_hip_graph_replay_correctly(ud):
         torch.cuda.synchronize()                                   # the program's own eager work between replays
         graph.replay()
         torch.cuda.synchronize()
-        ud.ud_gather_status(None)
+        ud.ud_gather_status(side.cuda_stream)                      # the record of the stream the gathers were captured on
         for D in widths:
             view = np.ascontiguousarray(t.numpy().ravel()[: N * D].reshape(N, D))
             assert np.array_equal(outs[D].cpu().numpy().view(np.uint32), oracle_bits(view, idx, oracle.F32)), (rep, D)
+    # a bad ID met during a replay is reported on that stream, and only there
+    idx = workloads.indices_uniform(70, M, N)
+    idx[1234] = N
+    didx.copy_(torch.from_numpy(idx))
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    ud.ud_gather_status(None)
+    with pytest.raises(ud.UdIndexError) as e:
+        ud.ud_gather_status(side.cuda_stream)
+    assert e.value.pos == 1234
+    ud.ud_gather_status(side.cuda_stream)                          # cleared
     t.free()
 
 
 
-@pytest.mark.parametrize("D", [1, 3, 16, 25, 100, 129, 602, 1031])
+@pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 16, 25, 100, 129, 255, 256, 257, 513, 602, 603, 1031, 4099])
 def test_device_resident_table_widths(ud, D):
-    # the HBM-resident plan differs (small lane groups, two rows in flight, streaming stores)
+    # an HBM-resident table takes the destination-aligned kernel by default; the source-aligned one
+    # (small lane groups, two rows in flight, streaming stores) must give the same bits.  Output
+    # offsets 0..3 elements put the output in every alignment class of the 16-byte chunk grid.
     N, M = 4001, 3777
     host = make_table(ud, N, D, ud.UD_F32, 900 + D)
     dev = host.to_device()
     idx = workloads.indices_uniform(90, M, N)
     idx[:2] = [0, N - 1]
-    got = run_gather(ud, dev, idx, ud.UD_F32, out_offset_elems=D % 4)
-    assert np.array_equal(got, oracle_bits(host.numpy(), idx, oracle.F32)), D
+    want = oracle_bits(host.numpy(), idx, oracle.F32)
+    for off in range(4):
+        assert np.array_equal(run_gather(ud, dev, idx, ud.UD_F32, out_offset_elems=off), want), (D, off)
+    got = run_gather(ud, dev, idx, ud.UD_F32, ud.ud_tuning(0, 0, 2, 0, ud.UD_TUNE_NT_STORE), out_offset_elems=D % 4)
+    assert np.array_equal(got, want), D
     dev.free()
     host.free()
+
+
+@pytest.mark.parametrize("P", [1, 2, 4])
+def test_destination_aligned_kernel_every_instantiation(ud, P):
+    # every (dtype, chunks per lane, streaming or plain store) form of the destination-aligned kernel, on host and
+    # HBM tables, for widths below, at and above one wavefront tile, with int32 and int64 IDs and a capped grid
+    N, M = 1201, 1103
+    cases = [(ud.UD_F32, ud.UD_F32, 77), (ud.UD_F32, ud.UD_F32, 2), (ud.UD_F32, ud.UD_F32, 1030),
+             (ud.UD_F16, ud.UD_F16_TO_F32, 301), (ud.UD_F16, ud.UD_F16_TO_F32, 5), (ud.UD_F16, ud.UD_F16, 75),
+             (ud.UD_F16, ud.UD_F16, 7), (ud.UD_F16, ud.UD_F16, 2051)]
+    for elem, dtype, D in cases:
+        t = make_table(ud, N, D, elem, 300 + D)
+        d = t.to_device()
+        for idt in (np.int64, np.int32):
+            idx = workloads.indices_uniform(9, M, N, idt)
+            idx[:2] = [0, N - 1]
+            want = oracle_bits(t.numpy(), idx, dtype)
+            for table in (t, d):
+                for flags in (ud.UD_TUNE_DEST_ALIGNED, ud.UD_TUNE_DEST_ALIGNED | ud.UD_TUNE_NT_STORE):
+                    for blocks in (0, 3):
+                        for off in (0, 1, 3):
+                            got = run_gather(ud, table, idx, dtype, ud.ud_tuning(0, P, 0, blocks, flags), out_offset_elems=off)
+                            assert np.array_equal(got, want), (dtype, D, idt, table is d, flags, blocks, off)
+        d.free()
+        t.free()
+
+
+def test_destination_aligned_kernel_reports_bad_ids_and_skips_their_rows(ud):
+    N, D, M = 500, 602, 4000
+    t = make_table(ud, N, D, ud.UD_F32, 22)
+    d = t.to_device()
+    idx = workloads.indices_uniform(23, M, N)
+    for bad_positions, bad_values in (([3111, 1717, 2500], [N, -1, N + 5]), ([0], [-7]), ([M - 1], [2**40])):
+        bad = idx.copy()
+        bad[bad_positions] = bad_values
+        out = torch.zeros((M, D), dtype=torch.float32, device="cuda")
+        s = torch.cuda.current_stream().cuda_stream
+        ud.ud_gather(d.device_ptr, N, D, ud.UD_F32, torch.from_numpy(bad).cuda().data_ptr(), ud.UD_I64, M, out.data_ptr(), s)
+        with pytest.raises(ud.UdIndexError) as e:
+            ud.ud_gather_status(s)
+        assert e.value.pos == min(bad_positions)
+        host = out.cpu().numpy()
+        good = np.ones(M, dtype=bool)
+        good[bad_positions] = False
+        assert np.array_equal(host[good], t.numpy()[idx[good]])
+        assert (host[~good] == 0).all()                              # bad rows are left unwritten, neighbours intact
+    d.free()
+    t.free()
 
 
 @pytest.mark.parametrize("D", [3, 301, 602])
@@ -579,7 +723,8 @@ def test_padded_table(ud, elem_name, dtype_name, D):
     obytes = 2 if dtype == ud.UD_F16 else 4
     want = np.empty((M, D), dtype=np.uint16 if obytes == 2 else np.uint32)
     oracle.gather_raw(t.host_ptr, N, D, dtype, idx, want, pitch=t.pitch)
-    assert np.array_equal(np.take(storage, idx, axis=0)[:, :D], want) or dtype == ud.UD_F16_TO_F32
+    if dtype != ud.UD_F16_TO_F32:                                  # bit copies: numpy on the padded storage agrees
+        assert np.array_equal(np.take(storage, idx, axis=0)[:, :D], want)
     for table in (t, t.to_device()):
         buf = torch.full(((M * D + 64) * obytes,), CANARY, dtype=torch.uint8, device="cuda")
         didx = torch.from_numpy(idx).cuda()

@@ -48,12 +48,15 @@ def test_random_gathers(ud):
         want = want.view(np.uint16 if obytes == 2 else np.uint32)
         u, p = SHAPES[int(rng.integers(0, len(SHAPES)))]
         lanes = int(2 ** rng.integers(0, 7))
-        flags = int(rng.choice([0, 1, 2, 3, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_XCD_REMAP, ud.UD_TUNE_ELEMENTWISE,
+        flags = int(rng.choice([0, 0, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_DEST_ALIGNED,
+                                ud.UD_TUNE_DEST_ALIGNED | ud.UD_TUNE_NT_STORE, ud.UD_TUNE_ELEMENTWISE,
                                 ud.UD_TUNE_ELEMENTWISE | ud.UD_TUNE_CIRCULAR_SHIFT, ud.UD_TUNE_SHARE_GPU]))
         blocks = int(rng.choice([0, 1, 3, 64]))
         tun = None if rng.random() < 0.25 else ud.ud_tuning(lanes, p, u, blocks, flags)
         if tun is not None and (flags & ud.UD_TUNE_SHARE_GPU):
             tun = ud.ud_tuning(0, 0, 0, blocks, flags)
+        if tun is not None and (flags & ud.UD_TUNE_DEST_ALIGNED):
+            tun = ud.ud_tuning(0, int(rng.choice([0, 1, 2, 4])), 0, blocks, flags)
         out_shift = int(rng.integers(0, 5))
         buf = torch.full(((M * D + out_shift + 32) * obytes,), 0x5A, dtype=torch.uint8, device="cuda")
         didx = torch.from_numpy(idx).cuda()
