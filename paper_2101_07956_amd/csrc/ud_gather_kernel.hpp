@@ -154,7 +154,16 @@ __device__ __forceinline__ void store_halves(uint16_t *d, u32x4 v, int lo, int h
 // list: the line is then fetched from HBM by one XCD's L2 once, instead of by
 // every XCD whose workgroups happen to hold a few of its IDs.  (For HBM-resident
 // tables group_iters is 1: there, several passes per wavefront cost up to 12%.)
-template <int DT, int U, int P, bool NTS>
+//
+// I64 (the ID type) is a template parameter, and the phases -- ID loads, table
+// loads, one wait, stores -- are kept apart in the source: with a run-time ID
+// type every ID load sits in a branch of its own, and a wait that the compiler
+// places inside a conditional block is needed again after every later branch,
+// so that the loads (and then the stores) of the rows in flight would wait for
+// one another.  For the same reason loaded chunks are kept in scalars: vectors
+// that are assigned conditionally end up copied between registers, with a wait
+// before each copy.
+template <int DT, int U, int P, bool NTS, bool I64>
 __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a, int lg)
 {
     constexpr int IN_ESZ = (DT == UD_F32) ? 4 : 2;      // table element bytes
@@ -189,8 +198,12 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
         for (int u = 0; u < U; ++u) {
             i[u] = rb + static_cast<int64_t>(u) * rpw + grp;
             r[u] = 0;
-            if (i[u] < a.M)
-                r[u] = load_id(a.idx, a.itype, i[u]);
+            if (i[u] < a.M) {
+                if constexpr (I64)
+                    r[u] = ((const UD_GLOBAL int64_t *)a.idx)[i[u]];
+                else
+                    r[u] = ((const UD_GLOBAL int32_t *)a.idx)[i[u]];
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -211,17 +224,19 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
         }
 
         for (int64_t cb = 0; cb < nch_bound; cb += span) {
-            u32x4 v[U][P];
+            uint32_t v[U][P][4];        // set, and later read, only where c < nch[u]
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
                     const int64_t c = cb + static_cast<int64_t>(p) * lpr + l;
-                    v[u][p] = u32x4{0, 0, 0, 0};
-                    if (c < nch[u])
-                        v[u][p] = ld_chunk(base[u] + c * 16);
+                    if (c < nch[u]) {
+                        const u32x4 t = ld_chunk(base[u] + c * 16);
+                        v[u][p][0] = t.x, v[u][p][1] = t.y, v[u][p][2] = t.z, v[u][p][3] = t.w;
+                    }
                 }
             }
+            __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): every load of this pass, once, outside the branches
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -236,17 +251,17 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
                     const int hi = left < EPC ? static_cast<int>(left) : EPC;
                     const int64_t o = i[u] * a.D + e0;
                     if constexpr (DT == UD_F32) {
-                        const uint32_t w[4] = {v[u][p].x, v[u][p].y, v[u][p].z, v[u][p].w};
+                        const uint32_t w[4] = {v[u][p][0], v[u][p][1], v[u][p][2], v[u][p][3]};
                         store_words<4, NTS>(static_cast<uint32_t *>(a.out) + o, w, lo, hi);
                     } else if constexpr (DT == UD_F16) {
-                        store_halves<NTS>(static_cast<uint16_t *>(a.out) + o, v[u][p], lo, hi);
+                        store_halves<NTS>(static_cast<uint16_t *>(a.out) + o,
+                                          u32x4{v[u][p][0], v[u][p][1], v[u][p][2], v[u][p][3]}, lo, hi);
                     } else {
-                        const uint32_t s[4] = {v[u][p].x, v[u][p].y, v[u][p].z, v[u][p].w};
                         uint32_t w[8];
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            w[2 * q] = widen_half(s[q] & 0xffffu);
-                            w[2 * q + 1] = widen_half(s[q] >> 16);
+                            w[2 * q] = widen_half(v[u][p][q] & 0xffffu);
+                            w[2 * q + 1] = widen_half(v[u][p][q] >> 16);
                         }
                         store_words<8, NTS>(static_cast<uint32_t *>(a.out) + o, w, lo, hi);
                     }
@@ -259,10 +274,15 @@ __global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a,
 template <int DT, int U, int P>
 hipError_t launch_nt(const GatherArgs &a, const Plan &p, int lg, dim3 grid, dim3 block, hipStream_t s)
 {
-    if (p.flags & UD_TUNE_NT_STORE)
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, true>), grid, block, 0, s, a, lg);
+    const bool nts = p.flags & UD_TUNE_NT_STORE, i64 = a.itype == UD_I64;
+    if (nts && i64)
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, true>), grid, block, 0, s, a, lg);
+    else if (nts)
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, true, false>), grid, block, 0, s, a, lg);
+    else if (i64)
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, true>), grid, block, 0, s, a, lg);
     else
-        hipLaunchKernelGGL((gather_chunked<DT, U, P, false>), grid, block, 0, s, a, lg);
+        hipLaunchKernelGGL((gather_chunked<DT, U, P, false, false>), grid, block, 0, s, a, lg);
     return hipGetLastError();
 }
 

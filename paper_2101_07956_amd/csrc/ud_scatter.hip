@@ -8,10 +8,10 @@
 // address, so that every full chunk is one aligned dwordx4 store and a
 // wavefront store instruction covers consecutive whole lines of the table.
 // Unlike a load, a store must not spill over the row's ends: of the partial head
-// and tail chunks only the row's own elements are loaded (element by element,
-// in the same load phase as the full chunks, so that nothing waits on them
-// alone) and stored.  The source rows (dense, in HBM) generally have another
-// alignment and are read with loads that are only element-aligned.
+// and tail chunks only the row's own elements are stored (masked, unrolled
+// element stores of the chunk that was loaded whole).  The source rows (dense,
+// in HBM) generally have another alignment and are read with loads that are
+// only element-aligned.
 #include "ud_gather_kernel.hpp"
 
 namespace ud {
@@ -26,29 +26,16 @@ __device__ __forceinline__ u32x4 ld_src_chunk(const char *p)
         return *(const UD_GLOBAL u32x4_a2 *)p;
 }
 
-// Elements [lo, hi) of the 16 bytes at p (the others read as zero and are never stored).
-template <int ESZ>
-__device__ __forceinline__ u32x4 ld_src_partial(const char *p, int lo, int hi)
-{
-    uint32_t w[4] = {0, 0, 0, 0};
-    if constexpr (ESZ == 4) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (q >= lo && q < hi)
-                w[q] = ((const UD_GLOBAL uint32_t *)p)[q];
-    } else {
-#pragma unroll
-        for (int q = 0; q < 8; ++q)
-            if (q >= lo && q < hi)
-                w[q >> 1] |= static_cast<uint32_t>(((const UD_GLOBAL uint16_t *)p)[q]) << ((q & 1) * 16);
-    }
-    return u32x4{w[0], w[1], w[2], w[3]};
-}
-
 // ESZ: element bytes (4 or 2).  U rows in flight per lane group, P chunks per
 // lane per row, lg = log2(lanes per row).  a.table is the destination, a.out
 // the dense source (reusing GatherArgs: `out` is read, `table` written).
-template <int ESZ, int U, int P>
+// I64: the ID type, fixed at compile time so that the ID loads of the U rows are
+// plain loads issued together (a run-time choice puts each in a branch, and
+// they then wait for one another).  The phases -- IDs, source loads, one wait,
+// full stores, partial stores -- are kept apart for the same reason: a wait
+// placed inside a conditional block by the compiler has to be repeated after
+// every later branch, where it also waits for the stores issued so far.
+template <int ESZ, int U, int P, bool I64>
 __global__ __launch_bounds__(kBlockThreads) void scatter_chunked(GatherArgs a, int lg)
 {
     constexpr int EPC = 16 / ESZ;
@@ -67,23 +54,32 @@ __global__ __launch_bounds__(kBlockThreads) void scatter_chunked(GatherArgs a, i
     const char *src = static_cast<const char *>(a.out);
 
     for (int64_t rb = wave * rows_per_iter; rb < a.M; rb += nwaves * rows_per_iter) {
-        int64_t i[U];
+        int64_t i[U], r[U];
         char *base[U];   // 16-byte aligned address at or below the destination row's first byte
         int head[U];
         int64_t nch[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             i[u] = rb + static_cast<int64_t>(u) * rpw + grp;
+            r[u] = 0;
+            if (i[u] < a.M) {
+                if constexpr (I64)
+                    r[u] = ((const UD_GLOBAL int64_t *)a.idx)[i[u]];
+                else
+                    r[u] = ((const UD_GLOBAL int32_t *)a.idx)[i[u]];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
             nch[u] = 0;
             base[u] = table;
             head[u] = 0;
             if (i[u] < a.M) {
-                const int64_t r = load_id(a.idx, a.itype, i[u]);
-                if (r < 0 || r >= a.N) {
+                if (r[u] < 0 || r[u] >= a.N) {
                     if (l == 0)
                         atomicMin(a.err, static_cast<unsigned long long>(i[u]));
                 } else {
-                    char *dst = table + r * a.pitch_bytes;
+                    char *dst = table + r[u] * a.pitch_bytes;
                     head[u] = static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 15u);
                     base[u] = dst - head[u];
                     nch[u] = (head[u] + row_bytes + 15) >> 4;
@@ -91,8 +87,9 @@ __global__ __launch_bounds__(kBlockThreads) void scatter_chunked(GatherArgs a, i
             }
         }
         for (int64_t cb = 0; cb < nch_bound; cb += span) {
-            u32x4 v[U][P];
+            uint32_t w[U][P][4];         // scalars, not vectors: conditionally assigned vectors end up copied around
             int lo[U][P], hi[U][P];      // elements of the chunk that belong to the row; lo >= hi: no chunk
+            bool edge[U][P];             // the chunk hangs over an end of the whole source: copied element by element
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -102,38 +99,60 @@ __global__ __launch_bounds__(kBlockThreads) void scatter_chunked(GatherArgs a, i
                     const int64_t left = a.D - e0;
                     lo[u][p] = e0 < 0 ? static_cast<int>(-e0) : 0;
                     hi[u][p] = c < nch[u] ? (left < EPC ? static_cast<int>(left) : EPC) : 0;
-                    v[u][p] = u32x4{0, 0, 0, 0};
-                    const char *s16 = src + (i[u] * a.D + e0) * ESZ;
+                    // A head or tail chunk is loaded whole like any other: what it reads beyond the row are
+                    // elements of the neighbouring source rows.  Only where those 16 bytes would begin before
+                    // the first or end after the last source element (the first and last rows of a launch;
+                    // with rows shorter than a chunk, their neighbours too) is the chunk copied element by
+                    // element instead.
+                    const int64_t s0 = i[u] * a.D + e0;           // first source element the whole-chunk load reads
+                    edge[u][p] = s0 < 0 || s0 + EPC > a.M * a.D;
+                    w[u][p][0] = w[u][p][1] = w[u][p][2] = w[u][p][3] = 0;
+                    if (lo[u][p] < hi[u][p] && !edge[u][p]) {
+                        const u32x4 t = ld_src_chunk<ESZ>(src + (i[u] * a.D + e0) * ESZ);
+                        w[u][p][0] = t.x, w[u][p][1] = t.y, w[u][p][2] = t.z, w[u][p][3] = t.w;
+                    }
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): all source loads, once, outside the branches
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    const int64_t c = cb + static_cast<int64_t>(p) * lpr + l;
                     if (lo[u][p] == 0 && hi[u][p] == EPC)
-                        v[u][p] = ld_src_chunk<ESZ>(s16);
-                    else if (lo[u][p] < hi[u][p])
-                        v[u][p] = ld_src_partial<ESZ>(s16, lo[u][p], hi[u][p]);
+                        *(UD_GLOBAL u32x4 *)(base[u] + c * 16) = u32x4{w[u][p][0], w[u][p][1], w[u][p][2], w[u][p][3]};
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
-                    if (lo[u][p] >= hi[u][p])
+                    if (lo[u][p] >= hi[u][p] || (lo[u][p] == 0 && hi[u][p] == EPC))
                         continue;
+                    // head or tail chunk: only the elements that belong to the row
                     const int64_t c = cb + static_cast<int64_t>(p) * lpr + l;
                     char *d16 = base[u] + c * 16;
-                    if (lo[u][p] == 0 && hi[u][p] == EPC) {
-                        *(UD_GLOBAL u32x4 *)d16 = v[u][p];
+                    if (edge[u][p]) {
+                        const int64_t e0 = c * EPC - head[u] / ESZ;
+                        const char *s16 = src + (i[u] * a.D + e0) * ESZ;
+                        for (int q = lo[u][p]; q < hi[u][p]; ++q) {
+                            if constexpr (ESZ == 4)
+                                ((UD_GLOBAL uint32_t *)d16)[q] = ((const UD_GLOBAL uint32_t *)s16)[q];
+                            else
+                                ((UD_GLOBAL uint16_t *)d16)[q] = ((const UD_GLOBAL uint16_t *)s16)[q];
+                        }
                         continue;
                     }
-                    // head or tail chunk: only the elements that belong to the row
-                    const uint32_t w[4] = {v[u][p].x, v[u][p].y, v[u][p].z, v[u][p].w};
                     if constexpr (ESZ == 4) {
 #pragma unroll
                         for (int q = 0; q < 4; ++q)
                             if (q >= lo[u][p] && q < hi[u][p])
-                                ((UD_GLOBAL uint32_t *)d16)[q] = w[q];
+                                ((UD_GLOBAL uint32_t *)d16)[q] = w[u][p][q];
                     } else {
 #pragma unroll
                         for (int q = 0; q < 8; ++q)
                             if (q >= lo[u][p] && q < hi[u][p])
-                                ((UD_GLOBAL uint16_t *)d16)[q] = static_cast<uint16_t>(w[q >> 1] >> ((q & 1) * 16));
+                                ((UD_GLOBAL uint16_t *)d16)[q] = static_cast<uint16_t>(w[u][p][q >> 1] >> ((q & 1) * 16));
                     }
                 }
             }
@@ -141,15 +160,24 @@ __global__ __launch_bounds__(kBlockThreads) void scatter_chunked(GatherArgs a, i
     }
 }
 
+template <int ESZ, int U, int P>
+static hipError_t launch_scatter_up(const GatherArgs &a, int lg, dim3 grid, hipStream_t s)
+{
+    if (a.itype == UD_I64)
+        hipLaunchKernelGGL((scatter_chunked<ESZ, U, P, true>), grid, dim3(kBlockThreads), 0, s, a, lg);
+    else
+        hipLaunchKernelGGL((scatter_chunked<ESZ, U, P, false>), grid, dim3(kBlockThreads), 0, s, a, lg);
+    return hipGetLastError();
+}
+
 template <int ESZ>
 static hipError_t launch_scatter_esz(const GatherArgs &a, const Plan &p, int lg, dim3 grid, hipStream_t s)
 {
     const int key = p.rows_in_flight * 10 + p.chunks_per_lane;
     switch (key) {
-#define UD_CASE(U_, P_)                                                                                          \
-    case U_ * 10 + P_:                                                                                           \
-        hipLaunchKernelGGL((scatter_chunked<ESZ, U_, P_>), grid, dim3(kBlockThreads), 0, s, a, lg);              \
-        return hipGetLastError();
+#define UD_CASE(U_, P_) \
+    case U_ * 10 + P_:  \
+        return launch_scatter_up<ESZ, U_, P_>(a, lg, grid, s);
         UD_CASE(1, 1)
         UD_CASE(2, 1)
         UD_CASE(4, 1)

@@ -175,3 +175,34 @@ def test_scatter_into_padded_table(ud, elem_name, D):
     ud.ud_gather_status(s)
     assert np.array_equal(storage, want)                      # data rows updated, padding and other rows untouched
     t.free()
+
+
+@pytest.mark.parametrize("esz,D", [(2, 1), (2, 3), (2, 5), (2, 7), (4, 1), (4, 2), (4, 3)])
+def test_rows_shorter_than_a_chunk_with_an_unaligned_table_base(ud, esz, D):
+    # rows of 2..14 bytes: a 16-byte destination chunk then spans several table rows, and the source
+    # elements beside a row's own may lie before the first or after the last source row; the source
+    # buffer is placed at the very start and the very end of its allocation so that an over-read shows
+    dtype = ud.UD_F32 if esz == 4 else ud.UD_F16
+    npdt = np.uint32 if esz == 4 else np.uint16
+    rng = np.random.default_rng(100 * esz + D)
+    s = torch.cuda.current_stream().cuda_stream
+    for shift in range(0, 16 // esz):
+        for M in (1, 2, 3, 17, 298):
+            N = 415
+            big = ud.Table(N + 8, D, dtype)
+            storage = np.frombuffer((__import__("ctypes").c_char * big.nbytes).from_address(big.host_ptr), dtype=npdt)
+            storage[:] = rng.integers(0, 2 ** (8 * esz), size=storage.size, dtype=np.uint64).astype(npdt)
+            want_all = storage.copy()
+            idx = rng.permutation(N)[:M].astype(np.int64)
+            end_row = 0 if shift % 2 else N - 1               # the first or the last table row, IDs kept distinct
+            if end_row in idx:
+                idx[idx == end_row] = idx[0]
+            idx[0] = end_row
+            src = rng.integers(0, 2 ** (8 * esz), size=(M, D), dtype=np.uint64).astype(npdt)
+            oracle.scatter(want_all[shift:shift + N * D].reshape(N, D), idx, src)
+            dsrc = torch.from_numpy(src.view(np.int32 if esz == 4 else np.int16)).cuda()
+            didx = torch.from_numpy(idx).cuda()
+            ud.ud_scatter(big.device_ptr + shift * esz, N, D, dtype, didx.data_ptr(), ud.UD_I64, M, dsrc.data_ptr(), s)
+            ud.ud_gather_status(s)
+            assert np.array_equal(storage, want_all), (esz, D, shift, M)
+            big.free()
