@@ -268,9 +268,11 @@ ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning
  * position i (position in idx, not the ID).  bad_pos is written in both cases and may be NULL.
  * The stream's record is read and cleared in one step, in stream order (a one-thread kernel on
  * `stream`), so errors of work on other streams are neither reported nor lost, and nothing runs on
- * the default stream.  Records are kept per stream for the first 63 streams that launch on a
- * device; all further streams share one record.  A stream handle that is destroyed and handed out
- * again by the runtime inherits its predecessor's record.  Gathers replayed from a HIP graph report
+ * the default stream.  A device keeps 63 per-stream records.  When all are taken, a stream that
+ * launches for the first time takes over the record of a stream that has launched nothing since its
+ * own last ud_gather_status call; if there is none, it shares one common record with all other
+ * streams in that position.  A stream handle that is destroyed and handed out again by the runtime
+ * inherits its predecessor's record.  A stream is driven by one thread at a time.  Gathers replayed from a HIP graph report
  * to the record of the stream they were captured on: synchronise the replay, then query that stream.
  * Not to be called while `stream` is being captured.
  */

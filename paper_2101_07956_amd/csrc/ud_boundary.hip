@@ -5,6 +5,7 @@
 // kernels live in ud_gather_*.hip.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -56,18 +57,27 @@ bool mul3_overflows(int64_t a, int64_t b, int64_t c, int64_t *r)
 
 // ID-error records.  Every device has a small table of error slots in HBM, one
 // per stream that has launched a gather or scatter (the kernels take the slot's
-// address and atomic-min the position of a bad ID into it).  A stream keeps its
-// slot for the life of the process; the table is allocated once, on the first
-// launch on that device, and nothing is allocated per call.  The last slot is
-// shared by all streams beyond the first kErrSlots - 1.
+// address and atomic-min the position of a bad ID into it).  The table is
+// allocated once, on the first launch on that device, and nothing is allocated
+// per call.  A stream keeps its slot until the table is full and another stream
+// needs one: then a slot whose owner has launched nothing since its last
+// ud_gather_status call (so all its work is complete and its record is clear) is
+// handed on.  If there is none, the last slot is shared by the streams that
+// found no slot of their own.
 constexpr int kMaxDevices = 64;
 constexpr int kErrSlots = 64;
 
 struct SlotTable {
     unsigned long long *words = nullptr;     // device memory, kErrSlots words
     hipStream_t owner[kErrSlots] = {};
+    std::atomic<bool> busy[kErrSlots] = {};  // launched on since the owner's last status call
     int used = 0;
 };
+
+// Bumped whenever a slot changes hands, so that per-thread shortcuts to a slot notice.
+std::atomic<unsigned long long> g_slot_generation{0};
+
+constexpr int kSlotTables = 1;                // slot tables a stream can hold a slot in
 
 struct DeviceState {
     SlotTable heap;                          // hipMalloc'd at the first launch
@@ -78,18 +88,24 @@ struct DeviceState {
 std::mutex g_err_mutex;
 DeviceState g_dev[kMaxDevices];
 
-// Index of `stream`'s slot in t, claiming a free one if `claim`; -1 if it has none.
+// Index of `stream`'s slot in t, claiming one if `claim`; -1 if it has none.
 int find_slot(SlotTable &t, hipStream_t stream, bool claim, bool share_last)
 {
     for (int k = 0; k < t.used; ++k)
         if (t.owner[k] == stream)
             return k;
+    if (!claim)
+        return (share_last && t.used == kErrSlots - 1) ? kErrSlots - 1 : -1;
     if (t.used < kErrSlots - 1) {
-        if (!claim)
-            return -1;
         t.owner[t.used] = stream;
         return t.used++;
     }
+    for (int k = 0; k < t.used; ++k)
+        if (!t.busy[k].load(std::memory_order_acquire)) {      // idle since its owner's last status call
+            t.owner[k] = stream;
+            g_slot_generation.fetch_add(1, std::memory_order_release);
+            return k;
+        }
     return share_last ? kErrSlots - 1 : -1;
 }
 
@@ -103,19 +119,25 @@ ud_status current_device(int *dev)
     return UD_OK;
 }
 
-// The error slot the kernels of a launch on `stream` report to.
-ud_status error_slot(hipStream_t stream, unsigned long long **w)
+// The error slot the kernels of a launch on `stream` report to.  `fixed` selects a second slot table
+// (none yet: always false).
+ud_status error_slot(hipStream_t stream, bool fixed, unsigned long long **w)
 {
     // the common case: the same thread launching on the same stream again
-    thread_local int last_dev = -1;
-    thread_local hipStream_t last_stream = nullptr;
-    thread_local unsigned long long *last_slot = nullptr;
+    thread_local int last_dev[2] = {-1, -1};
+    thread_local hipStream_t last_stream[2] = {nullptr, nullptr};
+    thread_local unsigned long long *last_slot[2] = {nullptr, nullptr};
+    thread_local std::atomic<bool> *last_busy[2] = {nullptr, nullptr};
+    thread_local unsigned long long last_generation[2] = {0, 0};
     int dev = 0;
     const ud_status st = current_device(&dev);
     if (st != UD_OK)
         return st;
-    if (last_slot && dev == last_dev && stream == last_stream) {
-        *w = last_slot;
+    const int f = fixed ? 1 : 0;
+    if (last_slot[f] && dev == last_dev[f] && stream == last_stream[f] &&
+        last_generation[f] == g_slot_generation.load(std::memory_order_acquire)) {
+        last_busy[f]->store(true, std::memory_order_release);
+        *w = last_slot[f];
         return UD_OK;
     }
     std::lock_guard<std::mutex> lock(g_err_mutex);
@@ -135,12 +157,20 @@ ud_status error_slot(hipStream_t stream, unsigned long long **w)
         }
         t.words = p;
     }
-    const int k = find_slot(t, stream, true, true);
+    const int k = find_slot(t, stream, true, !fixed);
+    if (k < 0) {
+        std::snprintf(g_hip_msg, sizeof g_hip_msg,
+                      "ud_gather_noalloc: all %d static error slots of this device belong to other streams", kErrSlots - 1);
+        return UD_ERR_UNSUPPORTED;
+    }
     *w = t.words + k;
+    t.busy[k].store(true, std::memory_order_release);
     if (k < kErrSlots - 1) {                 // the shared slot is not worth remembering
-        last_dev = dev;
-        last_stream = stream;
-        last_slot = *w;
+        last_dev[f] = dev;
+        last_stream[f] = stream;
+        last_slot[f] = *w;
+        last_busy[f] = &t.busy[k];
+        last_generation[f] = g_slot_generation.load(std::memory_order_acquire);
     }
     return UD_OK;
 }
@@ -443,7 +473,7 @@ ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning
 static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
                              const void *idx, ud_itype itype, int64_t M,
                              void *out, void *stream, const ud_tuning *tuning,
-                             const int32_t *slot, const char *cache)
+                             const int32_t *slot, const char *cache, bool fixed_slots = false)
 {
     if (N < 1 || D < 1 || M < 0 || pitch < D)
         return UD_ERR_INVALID_ARG;
@@ -543,7 +573,7 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pi
     a.cache = cache;
     a.group_iters = 1;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const ud_status es = error_slot(s, &a.err);
+    const ud_status es = error_slot(s, fixed_slots, &a.err);
     if (es != UD_OK)
         return es;
 
@@ -642,7 +672,7 @@ static ud_status scatter_impl(void *table, int64_t N, int64_t D, int64_t pitch, 
     a.out = const_cast<void *>(src);
     a.pitch_bytes = pitch * elem_bytes(dtype);
     a.group_iters = 1;
-    const ud_status es = error_slot(static_cast<hipStream_t>(stream), &a.err);
+    const ud_status es = error_slot(static_cast<hipStream_t>(stream), false, &a.err);
     if (es != UD_OK)
         return es;
     const hipError_t e = ud::launch_scatter(a, elem_bytes(dtype), plan, static_cast<hipStream_t>(stream));
@@ -760,16 +790,20 @@ ud_status ud_gather_status(void *stream, int64_t *bad_pos)
     ud_status st = current_device(&dev);
     if (st != UD_OK)
         return st;
-    unsigned long long *slot = nullptr, *res_host = nullptr, *res_dev = nullptr;
+    unsigned long long *slot[2] = {nullptr, nullptr}, *res_host[2] = {nullptr, nullptr}, *res_dev[2] = {nullptr, nullptr};
+    std::atomic<bool> *busy[2] = {nullptr, nullptr};
     {
         std::lock_guard<std::mutex> lock(g_err_mutex);
         DeviceState &d = g_dev[dev];
-        const int k = d.heap.words ? find_slot(d.heap, s, false, true) : -1;
-        if (k >= 0) {
+        SlotTable *tables[2] = {&d.heap, nullptr};
+        for (int f = 0; f < kSlotTables; ++f) {
+            const int k = tables[f]->words ? find_slot(*tables[f], s, false, f == 0) : -1;
+            if (k < 0)
+                continue;
             if (!d.result_host) {
-                // one pinned word per slot, so that status calls on different streams do not share one
+                // one pinned word per slot of either table, so that status calls on different streams do not share one
                 void *h = nullptr, *g = nullptr;
-                hipError_t e = hipHostMalloc(&h, kErrSlots * sizeof(unsigned long long), hipHostMallocMapped | hipHostMallocCoherent);
+                hipError_t e = hipHostMalloc(&h, 2 * kErrSlots * sizeof(unsigned long long), hipHostMallocMapped | hipHostMallocCoherent);
                 if (e == hipSuccess) {
                     e = hipHostGetDevicePointer(&g, h, 0);
                     if (e != hipSuccess)
@@ -780,28 +814,41 @@ ud_status ud_gather_status(void *stream, int64_t *bad_pos)
                 d.result_host = static_cast<unsigned long long *>(h);
                 d.result_dev = static_cast<unsigned long long *>(g);
             }
-            slot = d.heap.words + k;
-            res_host = d.result_host + k;
-            res_dev = d.result_dev + k;
+            slot[f] = tables[f]->words + k;
+            if (k < kErrSlots - 1)
+                busy[f] = &tables[f]->busy[k];
+            res_host[f] = d.result_host + f * kErrSlots + k;
+            res_dev[f] = d.result_dev + f * kErrSlots + k;
         }
     }
     hipError_t e;
-    if (slot) {
+    for (int f = 0; f < kSlotTables; ++f) {
+        if (!slot[f])
+            continue;
         // read and clear in one atomic step, ordered after this stream's gathers and before its next ones;
         // other streams' slots are not touched
-        *res_host = ud::kNoBadIndex;
-        e = ud::launch_fetch_and_reset(slot, res_dev, s);
+        *res_host[f] = ud::kNoBadIndex;
+        e = ud::launch_fetch_and_reset(slot[f], res_dev[f], s);
         if (e != hipSuccess)
             return hip_fail(e, "status kernel launch");
     }
     e = hipStreamSynchronize(s);
     if (e != hipSuccess)
         return hip_fail(e, "hipStreamSynchronize");
-    if (!slot)
-        return UD_OK;                       // nothing was ever launched on this stream
-    const unsigned long long v = *static_cast<volatile unsigned long long *>(res_host);
+    // everything this stream launched is complete and its records are clear: until its next launch its
+    // slots may be handed to another stream (a stream is driven by one thread at a time)
+    for (int f = 0; f < kSlotTables; ++f)
+        if (busy[f])
+            busy[f]->store(false, std::memory_order_release);
+    unsigned long long v = ud::kNoBadIndex;
+    for (int f = 0; f < kSlotTables; ++f)
+        if (slot[f]) {
+            const unsigned long long x = *static_cast<volatile unsigned long long *>(res_host[f]);
+            if (x < v)
+                v = x;
+        }
     if (v == ud::kNoBadIndex)
-        return UD_OK;
+        return UD_OK;                       // nothing bad, or nothing was ever launched on this stream
     if (bad_pos)
         *bad_pos = static_cast<int64_t>(v);
     return UD_ERR_INDEX_OUT_OF_RANGE;

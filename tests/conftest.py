@@ -34,3 +34,25 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+class RawStreams:
+    """n distinct HIP streams (default priority) made with hipStreamCreate: torch hands out streams from a
+    pool of 32 per device, so torch.cuda.Stream() objects cannot exceed the library's 63 per-stream slots."""
+
+    def __init__(self, n):
+        import ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipStreamCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipStreamDestroy.argtypes = [ctypes.c_void_p]
+        self.handles = []
+        for _ in range(n):
+            h = ctypes.c_void_p()
+            assert self.hip.hipStreamCreate(ctypes.byref(h)) == 0
+            self.handles.append(h.value)
+        assert len(set(self.handles)) == n
+
+    def close(self):
+        for h in self.handles:
+            assert self.hip.hipStreamDestroy(h) == 0
+        self.handles = []

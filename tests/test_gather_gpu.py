@@ -534,17 +534,34 @@ def test_more_streams_than_error_slots(ud):
     dbad = torch.from_numpy(bad).cuda()
     out = torch.empty((M, D), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
-    streams = [torch.cuda.Stream() for _ in range(70)]
-    for st in streams:
-        ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, out.data_ptr(), st.cuda_stream)
-        ud.ud_gather_status(st.cuda_stream)
+    from conftest import RawStreams
+    streams = RawStreams(140)
+    # used one after the other, each followed by its status call: slots are handed on, every stream has its own record
+    for st in streams.handles[:70]:
+        ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, out.data_ptr(), st)
+        ud.ud_gather_status(st)
         assert np.array_equal(out.cpu().numpy().view(np.uint32), want)
-    last = streams[-1]
-    ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, dbad.data_ptr(), ud.UD_I64, M, out.data_ptr(), last.cuda_stream)
-    with pytest.raises(ud.UdIndexError) as e:
-        ud.ud_gather_status(last.cuda_stream)
-    assert e.value.pos == 5
-    ud.ud_gather_status(last.cuda_stream)
+    # 70 streams with work outstanding at once: those beyond the table share one record
+    outs = torch.zeros((70, M, D), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    for k, st in enumerate(streams.handles[70:]):
+        ids = dbad if k in (3, 69) else didx
+        ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, ids.data_ptr(), ud.UD_I64, M, outs[k].data_ptr(), st)
+    reported = 0
+    for k, st in enumerate(streams.handles[70:]):
+        try:
+            ud.ud_gather_status(st)
+        except ud.UdIndexError as e:
+            assert e.pos == 5
+            reported += 1
+    assert 1 <= reported <= 2 + 7         # stream 3 reports its own; stream 69's may surface on any sharer of the common record
+    got = outs.cpu().numpy().view(np.uint32)
+    for k in range(70):
+        if k not in (3, 69):
+            assert np.array_equal(got[k], want), k
+    for st in streams.handles[70:]:
+        ud.ud_gather_status(st)
+    streams.close()
     t.free()
 
 
