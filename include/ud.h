@@ -136,6 +136,27 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
                     void *out, void *stream);
 
 /*
+ * ud_gather for callers that must not allocate: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same asynchrony, same results and the same
+ * ID-error reporting through ud_gather_status as ud_gather -- but the ID-error slots its kernels write
+ * to lie in a static device array of the library (64 slots of 8 bytes per GPU, held until the process
+ * ends) instead of the table ud_gather allocates on its first call.  This call never calls hipMalloc,
+ * hipFree or any allocating library routine, on its first call on a device either (that call only asks
+ * the runtime for the array's address on that device).
+ * The limit of the fixed array: 63 streams per device may have work of this call outstanding (launched
+ * and not yet followed by ud_gather_status on that stream); a call on a further stream is refused with
+ * UD_ERR_UNSUPPORTED (ud_last_hip_error tells why) and enqueues nothing.  The
+ * array is shared by all calls on a GPU and keeps its contents between calls: a stream's slot holds
+ * the smallest bad position seen since ud_gather_status last read (and thereby cleared) it.  Calls on
+ * one stream are ordered by the stream; calls that overlap on one GPU on different streams use
+ * different slots and do not disturb one another.  ud_gather_status itself pins a few host words on
+ * its first use on a device.
+ */
+ud_status ud_gather_noalloc(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                            const void *idx, ud_itype itype, int64_t M,
+                            void *out, void *stream);
+
+/*
  * ud_gather from a table whose rows are `pitch` elements apart (pitch >= D; the
  * elements D .. pitch-1 of each row are padding and are never read): out[i, j] =
  * conv(table[idx[i] * pitch + j]).  The output stays dense (row stride D).  This

@@ -27,7 +27,7 @@ UD_TUNE_CIRCULAR_SHIFT, UD_TUNE_SHARE_GPU, UD_TUNE_DEST_ALIGNED = 32, 128, 256
 #: every symbol include/ud.h declares
 EXPORTS = (
     "ud_alloc_table", "ud_table_to_device", "ud_table_host_ptr", "ud_table_device_ptr",
-    "ud_table_shape", "ud_table_pitch", "ud_free_table", "ud_gather", "ud_gather_pitched", "ud_gather_tuned", "ud_gather_plan",
+    "ud_table_shape", "ud_table_pitch", "ud_free_table", "ud_gather", "ud_gather_noalloc", "ud_gather_pitched", "ud_gather_tuned", "ud_gather_plan",
     "ud_gather_status", "ud_cache_create", "ud_cache_free", "ud_gather_cached",
     "ud_scatter", "ud_scatter_tuned", "ud_scatter_pitched", "ud_status_str", "ud_last_hip_error", "ud_build_id",
 )
@@ -76,6 +76,7 @@ _lib.ud_table_pitch.argtypes = [_vp, ctypes.POINTER(_i64)]
 _lib.ud_gather_pitched.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_free_table.argtypes = [_vp]
 _lib.ud_gather.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
+_lib.ud_gather_noalloc.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp]
 _lib.ud_gather_tuned.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _i64, _vp, _vp, ctypes.POINTER(ud_tuning)]
 _lib.ud_gather_plan.argtypes = [_vp, _i64, _int, ctypes.POINTER(ud_tuning)]
 _lib.ud_gather_status.argtypes = [_vp, ctypes.POINTER(_i64)]
@@ -165,6 +166,12 @@ def ud_gather(table: int, N: int, D: int, dtype: int, idx: int, itype: int, M: i
               stream: int | None = None) -> None:
     """Enqueue ``out[i, :] = conv(table[idx[i], :])``; all pointers are device addresses."""
     _check(_lib.ud_gather(table, N, D, dtype, idx, itype, M, out, stream), "ud_gather")
+
+
+def ud_gather_noalloc(table: int, N: int, D: int, dtype: int, idx: int, itype: int, M: int, out: int,
+                      stream: int | None = None) -> None:
+    """``ud_gather`` for callers that must not allocate (static device error slots)."""
+    _check(_lib.ud_gather_noalloc(table, N, D, dtype, idx, itype, M, out, stream), "ud_gather_noalloc")
 
 
 def ud_gather_tuned(table: int, N: int, D: int, dtype: int, idx: int, itype: int, M: int, out: int,

@@ -77,16 +77,30 @@ struct SlotTable {
 // Bumped whenever a slot changes hands, so that per-thread shortcuts to a slot notice.
 std::atomic<unsigned long long> g_slot_generation{0};
 
-constexpr int kSlotTables = 1;                // slot tables a stream can hold a slot in
+constexpr int kSlotTables = 2;                // slot tables a stream can hold a slot in
 
 struct DeviceState {
     SlotTable heap;                          // hipMalloc'd at the first launch
+    SlotTable fixed;                         // this device's copy of `scratch` (ud_gather_noalloc)
     unsigned long long *result_host = nullptr;   // pinned: where ud_gather_status receives a slot's value
     unsigned long long *result_dev = nullptr;    // the same words as the GPU addresses them
 };
 
 std::mutex g_err_mutex;
 DeviceState g_dev[kMaxDevices];
+
+// Error slots for ud_gather_noalloc: device memory that exists without any allocation call.  Every
+// GPU the library runs on holds its own copy of this array (512 bytes) until the process ends.  In
+// host code the name is only a stand-in for the symbol: the address the kernels use is asked for
+// once per device with hipGetSymbolAddress and kept in DeviceState::fixed.words.  The array comes
+// up holding "no bad ID" in every slot; afterwards it keeps what the last calls left, and each slot is
+// cleared when ud_gather_status reads it.
+#define UD_REP4(x) x, x, x, x
+#define UD_REP16(x) UD_REP4(x), UD_REP4(x), UD_REP4(x), UD_REP4(x)
+#define UD_REP64(x) UD_REP16(x), UD_REP16(x), UD_REP16(x), UD_REP16(x)
+static_assert(kErrSlots == 64, "the initialiser below names 64 slots");
+static __device__ __align__(256) unsigned long long scratch[kErrSlots] = {UD_REP64(0x7fffffffffffffffull)};
+static_assert(ud::kNoBadIndex == 0x7fffffffffffffffull, "scratch is initialised with the no-bad-ID sentinel");
 
 // Index of `stream`'s slot in t, claiming one if `claim`; -1 if it has none.
 int find_slot(SlotTable &t, hipStream_t stream, bool claim, bool share_last)
@@ -119,8 +133,9 @@ ud_status current_device(int *dev)
     return UD_OK;
 }
 
-// The error slot the kernels of a launch on `stream` report to.  `fixed` selects a second slot table
-// (none yet: always false).
+// The error slot the kernels of a launch on `stream` report to.  `fixed`: take it from the static
+// device array instead of the allocated table; this path allocates nothing and fails, rather than
+// share a slot, when every slot belongs to another stream.
 ud_status error_slot(hipStream_t stream, bool fixed, unsigned long long **w)
 {
     // the common case: the same thread launching on the same stream again
@@ -141,8 +156,15 @@ ud_status error_slot(hipStream_t stream, bool fixed, unsigned long long **w)
         return UD_OK;
     }
     std::lock_guard<std::mutex> lock(g_err_mutex);
-    SlotTable &t = g_dev[dev].heap;
-    if (!t.words) {
+    SlotTable &t = fixed ? g_dev[dev].fixed : g_dev[dev].heap;
+    if (!t.words && fixed) {
+        // once per device, with that device current: where this GPU keeps its copy of the array
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        t.words = static_cast<unsigned long long *>(p);
+    } else if (!t.words) {
         unsigned long long *p = nullptr;
         hipError_t e = hipMalloc(reinterpret_cast<void **>(&p), kErrSlots * sizeof *p);
         if (e != hipSuccess)
@@ -616,6 +638,13 @@ ud_status ud_gather(const void *table, int64_t N, int64_t D, ud_dtype dtype,
     return gather_impl(table, N, D, D, dtype, idx, itype, M, out, stream, env_tuning(), nullptr, nullptr);
 }
 
+ud_status ud_gather_noalloc(const void *table, int64_t N, int64_t D, ud_dtype dtype,
+                            const void *idx, ud_itype itype, int64_t M,
+                            void *out, void *stream)
+{
+    return gather_impl(table, N, D, D, dtype, idx, itype, M, out, stream, nullptr, nullptr, nullptr, true);
+}
+
 static ud_status scatter_impl(void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
                               const void *idx, ud_itype itype, int64_t M,
                               const void *src, void *stream, const ud_tuning *tuning)
@@ -790,12 +819,13 @@ ud_status ud_gather_status(void *stream, int64_t *bad_pos)
     ud_status st = current_device(&dev);
     if (st != UD_OK)
         return st;
+    // the stream may hold a slot in the allocated table, in the static one (ud_gather_noalloc), or in both
     unsigned long long *slot[2] = {nullptr, nullptr}, *res_host[2] = {nullptr, nullptr}, *res_dev[2] = {nullptr, nullptr};
     std::atomic<bool> *busy[2] = {nullptr, nullptr};
     {
         std::lock_guard<std::mutex> lock(g_err_mutex);
         DeviceState &d = g_dev[dev];
-        SlotTable *tables[2] = {&d.heap, nullptr};
+        SlotTable *tables[2] = {&d.heap, &d.fixed};
         for (int f = 0; f < kSlotTables; ++f) {
             const int k = tables[f]->words ? find_slot(*tables[f], s, false, f == 0) : -1;
             if (k < 0)
