@@ -629,7 +629,7 @@ def wl_overlap(env, quick=False, table=None):
         return f
 
     T = ud.ud_tuning
-    shapes = [("auto_512wg", None), ("128wg", T(0, 0, 0, 128, 0)), ("64wg", T(0, 0, 0, 64, 0)),
+    shapes = [("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("128wg", T(0, 0, 0, 128, 0)), ("64wg", T(0, 0, 0, 64, 0)),
               ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU)), ("32wg_of_1024", T(0, 0, 0, 32, ud.UD_TUNE_BIG_BLOCKS))]
     if not quick:
         shapes += [("256wg", T(0, 0, 0, 256, 0)), ("64wg_4rows_in_flight", T(0, 1, 4, 64, 0)),
@@ -652,7 +652,7 @@ def wl_overlap(env, quick=False, table=None):
     consumer["passes"] = max(1, round(8 * t_c / t_e))
     t_e = timed(only_compute) / nb
     elementwise = {"compute_only_ms": round(t_e, 3), "passes": consumer["passes"]}
-    for name, tun in (("auto_512wg", None), ("128wg", T(0, 0, 0, 128, 0)), ("64wg", T(0, 0, 0, 64, 0)),
+    for name, tun in (("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("64wg", T(0, 0, 0, 64, 0)),
                       ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU))):
         tg = timed(only_gather(tun)) / nb
         to = timed(overlapped(tun)) / nb

@@ -232,13 +232,19 @@ enum {
                                    64 workgroups for rows of 1 KiB or more, 128 below (unless max_blocks is given),
                                    and enough rows in flight per lane group to keep about 1 KiB per wavefront on
                                    the link; 94-100% of the stand-alone rate */
-    UD_TUNE_DEST_ALIGNED = 256u /* the kernel that cuts the OUTPUT, taken as one dense stream, into aligned 16-byte
+    UD_TUNE_DEST_ALIGNED = 256u, /* the kernel that cuts the OUTPUT, taken as one dense stream, into aligned 16-byte
                                    chunks (every store an aligned dwordx4, every output line written whole by one
                                    wavefront) and reads the table with element-aligned loads.  The automatic
                                    choice for tables in HBM, where the gather is bound by HBM bandwidth; tables
                                    read over the host link use the source-aligned kernel (flag clear).  Uses
                                    chunks_per_lane and max_blocks; lanes_per_row and rows_in_flight are ignored.
                                    Not combinable with ELEMENTWISE, BIG_BLOCKS or SHARE_GPU */
+    UD_TUNE_FLAT_SOURCE = 512u  /* ud_scatter_tuned only: the scatter kernel that cuts the dense SOURCE into aligned
+                                   16-byte chunks, one per lane (no idle lanes whatever the width), and writes the table
+                                   rows with element-aligned stores.  The automatic choice for tables in HBM; tables
+                                   behind the host link take the kernel that writes whole aligned chunks of the table
+                                   (flag clear).  Uses chunks_per_lane (1, 2 or 4) and max_blocks; may be combined with
+                                   UD_TUNE_NT_STORE (streaming stores to the table) */
 };
 
 /* ud_gather with explicit kernel parameters (for the tuning loop and for tests that
@@ -274,7 +280,7 @@ ud_status ud_scatter(void *table, int64_t N, int64_t D, ud_dtype dtype,
 ud_status ud_scatter_pitched(void *table, int64_t N, int64_t D, int64_t pitch, ud_dtype dtype,
                              const void *idx, ud_itype itype, int64_t M,
                              const void *src, void *stream);
-/* ud_scatter with explicit kernel parameters (tuning->flags must be 0). */
+/* ud_scatter with explicit kernel parameters (tuning->flags: 0, UD_TUNE_FLAT_SOURCE, or that with UD_TUNE_NT_STORE). */
 ud_status ud_scatter_tuned(void *table, int64_t N, int64_t D, ud_dtype dtype,
                            const void *idx, ud_itype itype, int64_t M,
                            const void *src, void *stream, const ud_tuning *tuning);

@@ -27,7 +27,7 @@
 // computed once in scalar registers, per-chunk work is 32-bit, and the row of a
 // tile's first element comes from one double-precision multiply instead of a
 // 64-bit division.  Results are bit-identical to the chunked kernel's.
-#include "ud_gather_kernel.hpp"
+#include "ud_flat.hpp"
 
 namespace ud {
 
@@ -62,29 +62,6 @@ __device__ __forceinline__ uint32_t load_element(const char *row, uint32_t j)
         return ((const UD_GLOBAL uint16_t *)row)[j];
     else
         return widen_half(((const UD_GLOBAL uint16_t *)row)[j]);
-}
-
-// What the host works out once per launch.
-struct FlatArgs {
-    char *obase;        // 16-byte boundary at or below out[0]: chunk c is obase + 16 c
-    int64_t nchunks;    // chunks that overlap the output
-    int64_t ntiles;
-    int64_t pre;        // vrows * D - shift: chunk-grid element x is element x + pre counted from row -vrows
-    int64_t vrows;      // virtual rows before row 0 that hold the `shift` elements preceding out[0]
-    double rcp_d;       // 1 / D
-    float rcp_d_f;
-};
-
-// ID number k (>= 0) counted from `base`, which need not be a valid address itself.  The ID type is a
-// template parameter: a run-time choice would put every load in a branch of its own, and the loads of a
-// tile would then wait for one another.
-template <bool I64>
-__device__ __forceinline__ int64_t load_id_at(const char *base, uint32_t k)
-{
-    if constexpr (I64)
-        return ((const UD_GLOBAL int64_t *)base)[k];
-    else
-        return static_cast<int64_t>(((const UD_GLOBAL int32_t *)base)[k]);
 }
 
 // A chunk that lies across a row end, put together from two loads: A = the last 16 output bytes' worth of
@@ -183,18 +160,9 @@ __global__ __launch_bounds__(kBlockThreads) void gather_flat(GatherArgs a, FlatA
 
     for (int64_t t = wave; t < f.ntiles; t += nwaves) {
         // ---- per tile, the same in every lane: row i0 and column j0 of the tile's first element ----
-        const int64_t y0 = t * (TILE * EPC) + f.pre;                 // >= 0, counted from row -vrows
-        int64_t q0 = static_cast<int64_t>(static_cast<double>(y0) * f.rcp_d);
-        int64_t rem = y0 - q0 * a.D;                                 // the double quotient is off by one at most
-        if (rem < 0) {
-            --q0;
-            rem += a.D;
-        } else if (rem >= a.D) {
-            ++q0;
-            rem -= a.D;
-        }
-        const int64_t i0 = q0 - f.vrows;
-        const uint32_t j0 = static_cast<uint32_t>(rem);
+        int64_t i0;
+        uint32_t j0;
+        tile_origin(f, a.D, t * (TILE * EPC), &i0, &j0);
         const int64_t left = f.nchunks - t * TILE;                   // chunks from this tile's first to the last
         const uint32_t nch_t = left < TILE ? static_cast<uint32_t>(left) : TILE;
         char *const ob = f.obase + t * (TILE * 16);
@@ -235,16 +203,7 @@ __global__ __launch_bounds__(kBlockThreads) void gather_flat(GatherArgs a, FlatA
         for (int p = 0; p < P; ++p) {
             const uint32_t cl = p * 64 + lane;
             const uint32_t y = j0 + cl * EPC;
-            if (D >= TILE * EPC) {
-                di[p] = y >= D ? 1u : 0u;
-            } else {
-                // y < 2 * TILE * EPC <= 4096: the float quotient is off by one at most
-                di[p] = static_cast<uint32_t>(static_cast<float>(y) * f.rcp_d_f);
-                if (di[p] * D > y)
-                    --di[p];
-                else if (y - di[p] * D >= D)
-                    ++di[p];
-            }
+            di[p] = rows_ahead<TILE * EPC>(y, D, f.rcp_d_f);
             j[p] = y - di[p] * D;
             split[p] = (D - j[p] < static_cast<uint32_t>(EPC)) ? static_cast<int>(D - j[p]) : EPC;
             ida[p] = idb[p] = 0;
@@ -382,21 +341,10 @@ template <int DT>
 static hipError_t launch_flat_dt(const GatherArgs &a, const Plan &p, hipStream_t s)
 {
     constexpr int OUT_ESZ = (DT == UD_F16) ? 2 : 4;
-    constexpr int EPC = 16 / OUT_ESZ;
     const int P = p.chunks_per_lane;
     if (P != 1 && P != 2 && P != 4)
         return hipErrorInvalidValue;
-    FlatArgs f{};
-    const uintptr_t out_addr = reinterpret_cast<uintptr_t>(a.out);
-    const int64_t shift = static_cast<int64_t>(out_addr & 15u) / OUT_ESZ;
-    f.obase = reinterpret_cast<char *>(out_addr - static_cast<uintptr_t>(shift) * OUT_ESZ);
-    f.vrows = (shift + a.D - 1) / a.D;
-    f.pre = f.vrows * a.D - shift;
-    f.nchunks = (shift + a.M * a.D + EPC - 1) / EPC;
-    const int64_t tile = 64 * P;
-    f.ntiles = (f.nchunks + tile - 1) / tile;
-    f.rcp_d = 1.0 / static_cast<double>(a.D);
-    f.rcp_d_f = 1.0f / static_cast<float>(a.D);
+    const FlatArgs f = make_flat_args(a.out, a.M, a.D, OUT_ESZ, P);
     int64_t blocks = (f.ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > p.max_blocks)
         blocks = p.max_blocks;

@@ -63,6 +63,10 @@ hipError_t launch_fill_slots(const int64_t *rows, int64_t n, int32_t *slot, hipS
 // source, a.table the destination.  elem_bytes is 4 or 2.
 hipError_t launch_scatter(const GatherArgs &a, int elem_bytes, const Plan &p, hipStream_t s);
 
+// Enqueue the source-aligned scatter (the dense source seen as one stream of 16-byte chunks): p.chunks_per_lane
+// (1, 2 or 4) and p.max_blocks.  hipErrorInvalidValue outside what flat_supports covers.
+hipError_t launch_scatter_flat(const GatherArgs &a, int elem_bytes, const Plan &p, hipStream_t s);
+
 // Enqueue the one-lane-per-element gather.
 hipError_t launch_elementwise(const GatherArgs &a, int dtype, const Plan &p, hipStream_t s);
 

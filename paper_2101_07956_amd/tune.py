@@ -69,7 +69,7 @@ def _amplification(path: str, scale: float) -> int:
     return 0
 
 
-KERNEL_MARKS = ("gather_chunked", "gather_flat", "gather_elementwise", "scatter_chunked")
+KERNEL_MARKS = ("gather_chunked", "gather_flat", "gather_elementwise", "scatter_chunked", "scatter_flat")
 REPLAY_LAUNCHES = 3          # per shape: the first is a warm-up, counters are read from the last
 
 
@@ -109,6 +109,9 @@ def replay_shapes(ud):
     for where in ("host", "hbm"):
         for D in (16, 100, 128, 602):
             shapes.append((f"scatter {where} f32 D={D} auto", "scatter", ud.UD_F32, D, where, "perm", None))
+    for D in (100, 602):
+        shapes.append((f"scatter hbm f32 D={D} row-per-lane-group kernel", "scatter", ud.UD_F32, D, "hbm", "perm", T(0, 0, 0, 0, 0)))
+    shapes.append(("scatter hbm f32 D=96 auto (384-byte rows: whole lines)", "scatter", ud.UD_F32, 96, "hbm", "perm", None))
     return shapes
 
 
@@ -221,7 +224,8 @@ def _read_counter_csv(path: str):
     return per_dispatch[marker], [per_dispatch[d] for d in ours], [names[d] for d in ours]
 
 
-def _summarise(timing_path: str, csv_paths, out_path, traffic_note=None) -> int:
+def _summarise(timing_path: str, csv_paths, out_path, traffic_note=None, only=None, note=None) -> int:
+    import re
     timing = json.load(open(timing_path))
     shapes = timing["shapes"]
     counters = [{} for _ in shapes]
@@ -242,6 +246,13 @@ def _summarise(timing_path: str, csv_paths, out_path, traffic_note=None) -> int:
     wscale = gib_kib / copy_vals["WRITE_SIZE"] if copy_vals.get("WRITE_SIZE") else None
     lines = []
     w = lines.append
+    if note:
+        w(f"# {note}")
+    w("# made by: python3 -m paper_2101_07956_amd.tune --summarise <timing> <counter files...>, from")
+    w("#   python3 -m paper_2101_07956_amd.tune --replay --json <timing>            (plain run: HIP-event times)")
+    for path in csv_paths:
+        found = sorted({r["Counter_Name"] for r in csv.DictReader(open(path))})
+        w(f"#   rocprofv3 --pmc {' '.join(found)} -f csv -d <dir> -o <name> -- python3 -m paper_2101_07956_amd.tune --replay")
     w(f"# Tuning table of the row-gather library on {timing['device']} (build {timing['build_id']}): one row per launch shape.")
     w(f"# {timing['rows_per_launch']:,} rows per launch, tables of {timing['table_rows']:,} rows; HIP-event time of an unprofiled run; peaks of that run:")
     w(f"#   host link {timing['h2d_peak_GBps']:.2f} GB/s (pinned hipMemcpy H2D), {timing['d2h_peak_GBps']:.2f} GB/s (D2H, for the write direction); HBM {HBM_PEAK_GBPS:.0f} GB/s (published)")
@@ -273,6 +284,8 @@ def _summarise(timing_path: str, csv_paths, out_path, traffic_note=None) -> int:
         hdr += f" {c.replace('_sum', ''):>22s}"
     w(hdr)
     for s, c, kn in zip(shapes, counters, kernels):
+        if only and not re.search(only, s["name"]):
+            continue
         gbps = s["useful_bytes"] / s["ms"] / 1e6
         line = f"{s['name']:64s} {s['ms']:9.4f} {gbps:9.2f} {100 * gbps / s['peak_GBps']:6.1f} {s['peak_kind']:>9s}"
         read_row = s["row_bytes_in"] if s["kind"] != "scatter" else s["row_bytes_out"]
@@ -298,7 +311,7 @@ def _summarise(timing_path: str, csv_paths, out_path, traffic_note=None) -> int:
     w("")
     w("# kernel of each shape (as the profiler names it):")
     for s, kn in zip(shapes, kernels):
-        if kn:
+        if kn and not (only and not re.search(only, s["name"])):
             w(f"#   {s['name']:64s} {kn.replace('void ud::', '').replace('(ud::GatherArgs, int)', '').replace('(ud::GatherArgs, ud::FlatArgs)', '').replace('(ud::GatherArgs)', '')}")
     if traffic_note and fscale and wscale:
         # what bench.py prints as roofline.traffic: the D=602 gathers' measured fabric traffic, with the launch shape
@@ -331,9 +344,11 @@ def _short(name: str) -> str:
     return name
 
 
-def _kernel_stats(paths, out_path) -> int:
+def _kernel_stats(paths, out_path, note=None) -> int:
     """rocprofv3's *_kernel_stats.csv (and, if given, *_kernel_trace.csv) as a short text table."""
-    lines = [f"{'kernel':78s} {'calls':>6s} {'avg_ms':>10s} {'min_ms':>10s} {'max_ms':>10s} {'pct':>6s}"]
+    lines = ([f"# {note}"] if note else []) + [
+        "# made by: python3 -m paper_2101_07956_amd.tune --kernel-stats <..._kernel_stats.csv> <..._kernel_trace.csv>", "",
+        f"{'kernel':78s} {'calls':>6s} {'avg_ms':>10s} {'min_ms':>10s} {'max_ms':>10s} {'pct':>6s}"]
     for r in csv.DictReader(open(paths[0])):
         n = _short(r["Name"])
         lines.append(f"{n[:78]:78s} {r['Calls']:>6s} {float(r['AverageNs']) / 1e6:10.4f} {float(r['MinNs']) / 1e6:10.4f} "
@@ -372,15 +387,17 @@ def main() -> int:
     ap.add_argument("--out", default=None, help="with --summarise: write the table here instead of stdout")
     ap.add_argument("--kernel-stats", nargs="+", default=None, metavar="CSV",
                     help="rocprofv3 *_kernel_stats.csv [and *_kernel_trace.csv]: print them as a short table")
+    ap.add_argument("--only", default=None, metavar="REGEX", help="with --summarise: keep the shapes whose name matches")
+    ap.add_argument("--note", default=None, help="with --summarise / --kernel-stats: first line of the output")
     ap.add_argument("--traffic-note", default=None, metavar="FILE",
                     help="with --summarise (FETCH_SIZE and WRITE_SIZE files given): also write the D=602 traffic figures bench.py reports")
     args = ap.parse_args()
     if args.amplification:
         return _amplification(args.amplification, args.scale)
     if args.kernel_stats:
-        return _kernel_stats(args.kernel_stats, args.out)
+        return _kernel_stats(args.kernel_stats, args.out, args.note)
     if args.summarise:
-        return _summarise(args.summarise[0], args.summarise[1:], args.out, args.traffic_note)
+        return _summarise(args.summarise[0], args.summarise[1:], args.out, args.traffic_note, args.only, args.note)
     if args.replay:
         return _replay(args)
 
@@ -411,16 +428,16 @@ def main() -> int:
     stream = torch.cuda.current_stream().cuda_stream
 
     def rate(tptr, D, tun, useful):
+        # launches back to back between one pair of events: sub-millisecond kernels measured one at a time,
+        # with a host round trip between them, read several percent low
         ud.ud_gather_tuned(tptr, N, D, ud.UD_F32, idx.data_ptr(), ud.UD_I64, M, out.data_ptr(), stream, tun)
-        ts = []
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for _ in range(args.reps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
             ud.ud_gather_tuned(tptr, N, D, ud.UD_F32, idx.data_ptr(), ud.UD_I64, M, out.data_ptr(), stream, tun)
-            e1.record()
-            e1.synchronize()
-            ts.append(e0.elapsed_time(e1))
-        return useful / sorted(ts)[len(ts) // 2] / 1e6
+        e1.record()
+        e1.synchronize()
+        return useful / (e0.elapsed_time(e1) / args.reps) / 1e6
 
     shapes = [(u, p) for u in (1, 2, 4) for p in (1, 2, 3, 4) if u * p <= 8 and (u, p) != (4, 2)]
     everything = []
@@ -439,6 +456,12 @@ def main() -> int:
                             g = rate(tptr, D, ud.ud_tuning(lanes, p, u, blocks, flags), useful)
                             res.append({"GBps": round(g, 2), "lanes": lanes, "rows_in_flight": u, "chunks_per_lane": p,
                                         "max_blocks": blocks, "flags": flags})
+            if where == "hbm":
+                for p in (1, 2, 4):
+                    for flags in (ud.UD_TUNE_DEST_ALIGNED, ud.UD_TUNE_DEST_ALIGNED | ud.UD_TUNE_NT_STORE):
+                        g = rate(tptr, D, ud.ud_tuning(0, p, 0, 0, flags), useful)
+                        res.append({"GBps": round(g, 2), "lanes": 0, "rows_in_flight": 0, "chunks_per_lane": p, "max_blocks": 0,
+                                    "flags": flags})
             res.sort(key=lambda r: -r["GBps"])
             auto_plan = ud.ud_gather_plan(tptr, D, ud.UD_F32)
             auto = rate(tptr, D, None, useful)

@@ -69,6 +69,11 @@ def test_scatter_rejects_bad_arguments(ud):
     a = list(ok_args)
     a[6] = 0
     assert rs("ud_scatter", *a) == ud.UD_OK                 # M == 0: no-op, no device needed
+    T = ud.ud_tuning
+    for tun, want in ((T(0, 0, 0, 0, ud.UD_TUNE_FLAT_SOURCE), ud.UD_OK), (T(0, 3, 0, 0, ud.UD_TUNE_FLAT_SOURCE), ud.UD_ERR_UNSUPPORTED),
+                      (T(0, 0, 0, 0, ud.UD_TUNE_NT_STORE), inv), (T(3, 0, 0, 0, 0), inv),
+                      (T(0, 0, 0, 0, ud.UD_TUNE_FLAT_SOURCE | ud.UD_TUNE_NT_STORE), ud.UD_OK)):
+        assert rs("ud_scatter_tuned", *a, ctypes.byref(tun)) == want
 
 
 def test_empty_gather_is_ok_without_a_device(ud):

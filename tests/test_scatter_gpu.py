@@ -206,3 +206,71 @@ def test_rows_shorter_than_a_chunk_with_an_unaligned_table_base(ud, esz, D):
             ud.ud_gather_status(s)
             assert np.array_equal(storage, want_all), (esz, D, shift, M)
             big.free()
+
+
+# ---- the source-aligned kernel (automatic for tables in HBM; UD_TUNE_FLAT_SOURCE elsewhere) ----
+
+@pytest.mark.parametrize("P", [1, 2, 4])
+def test_source_aligned_scatter_every_instantiation(ud, P):
+    # fp32 and fp16, int64 and int32 IDs, widths below / at / above a wavefront tile and rows shorter than a chunk,
+    # host and HBM tables, source buffers at every alignment of the 16-byte chunk grid, capped grid
+    N, M = 1201, 1103
+    s = torch.cuda.current_stream().cuda_stream
+    for elem, D in ((ud.UD_F32, 77), (ud.UD_F32, 2), (ud.UD_F32, 1030), (ud.UD_F32, 100), (ud.UD_F16, 75), (ud.UD_F16, 7),
+                    (ud.UD_F16, 2051), (ud.UD_F16, 301)):
+        esz = 4 if elem == ud.UD_F32 else 2
+        fill = workloads.uniform_f32 if elem == ud.UD_F32 else workloads.normal_f16
+        host = ud.Table(N, D, elem)
+        host.numpy()[:] = fill(1, N, D)
+        dev = host.to_device()
+        for idt in (np.int64, np.int32):
+            idx = distinct_ids(D + P, M, N, idt)
+            idx[:2] = [0, N - 1] if 0 not in idx[2:] and N - 1 not in idx[2:] else idx[:2]
+            src = fill(3 + P, M, D)
+            want = host.numpy().copy()
+            oracle.scatter(want, idx, src)
+            didx = torch.from_numpy(idx).cuda()
+            for off in (0, 1, 16 // esz - 1):
+                buf = torch.zeros(M * D + 16, dtype=torch.int32 if esz == 4 else torch.int16, device="cuda")
+                buf[off:off + M * D] = torch.from_numpy(src.view(np.int32 if esz == 4 else np.int16).ravel()).cuda()
+                for blocks, nt in ((0, 0), (3, ud.UD_TUNE_NT_STORE)):
+                    tun = ud.ud_tuning(0, P, 0, blocks, ud.UD_TUNE_FLAT_SOURCE | nt)
+                    # host table through the flag
+                    host.numpy()[:] = fill(1, N, D)
+                    ud.ud_scatter(host.device_ptr, N, D, elem, didx.data_ptr(), ud.UD_I64 if idt == np.int64 else ud.UD_I32, M,
+                                  buf.data_ptr() + off * esz, s, tun)
+                    ud.ud_gather_status(s)
+                    assert np.array_equal(bits(host.numpy()), bits(want)), (elem, D, idt, off, blocks)
+            # HBM table: the automatic choice; read back with the gather
+            ud.ud_scatter(dev.device_ptr, N, D, elem, didx.data_ptr(), ud.UD_I64 if idt == np.int64 else ud.UD_I32, M,
+                          torch.from_numpy(src.view(np.int32 if esz == 4 else np.int16)).cuda().data_ptr(), s)
+            allrows = torch.arange(N, dtype=torch.int64, device="cuda")
+            out = torch.empty((N, D), dtype=torch.float32 if esz == 4 else torch.float16, device="cuda")
+            ud.ud_gather(dev.device_ptr, N, D, elem, allrows.data_ptr(), ud.UD_I64, N, out.data_ptr(), s)
+            ud.ud_gather_status(s)
+            assert np.array_equal(bits(out.cpu().numpy()), bits(want)), (elem, D, idt, "hbm")
+            # put the HBM copy back for the next ID type
+            host.numpy()[:] = fill(1, N, D)
+            dev.free()
+            dev = host.to_device()
+        dev.free()
+        host.free()
+
+
+def test_source_aligned_scatter_skips_and_reports_bad_ids(ud):
+    N, D, M = 300, 602, 200
+    t = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_uniform_f32(t.host_ptr, 15, N * D)
+    want = t.numpy().copy()
+    idx = distinct_ids(16, M, N)
+    src = workloads.uniform_f32(17, M, D)
+    bad = idx.copy()
+    bad[[150, 20]] = [N, -1]
+    with pytest.raises(ud.UdIndexError) as e:
+        run_scatter(ud, t, bad, src, ud.ud_tuning(0, 0, 0, 0, ud.UD_TUNE_FLAT_SOURCE))
+    assert e.value.pos == 20
+    good = np.ones(M, dtype=bool)
+    good[[150, 20]] = False
+    oracle.scatter(want, idx[good], src[good])
+    assert np.array_equal(bits(t.numpy()), bits(want))          # rows of bad IDs untouched, every other row written
+    t.free()
