@@ -25,6 +25,12 @@ int main(void)
         return 6;
     if (ud_free_table(NULL) != UD_OK || ud_cache_free(NULL) != UD_OK)
         return 7;
+    if (ud_gather_noalloc(NULL, 4, 4, UD_F32, NULL, UD_I64, 0, NULL, NULL) != UD_OK)
+        return 8;
+    if (ud_gather_noalloc((const void *)0x1000, 4, 4, UD_F32, NULL, UD_I64, 1, (void *)0x2000, NULL) != UD_ERR_INVALID_ARG)
+        return 9;
+    if (strlen(ud_build_id()) == 0)
+        return 10;
     (void)bad;
     printf("c abi ok\n");
     return 0;

@@ -274,3 +274,41 @@ def test_source_aligned_scatter_skips_and_reports_bad_ids(ud):
     oracle.scatter(want, idx[good], src[good])
     assert np.array_equal(bits(t.numpy()), bits(want))          # rows of bad IDs untouched, every other row written
     t.free()
+
+
+def test_full_size_scatter_into_the_benchmark_table(ud):
+    # the write direction at the benchmark's size: 1,000,000 distinct rows x 602 fp32 into the 4,000,000-row
+    # host-pinned table (9.6 GB), the whole table compared with the oracle's; then the same into its HBM copy,
+    # read back through the gather
+    N, D, M = 4_000_000, 602, 1_000_000
+    t = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_uniform_f32(t.host_ptr, 8, N * D)
+    dev = t.to_device()
+    idx = np.random.default_rng(8).permutation(N)[:M].astype(np.int64)
+    if 0 not in idx:
+        idx[0] = 0                                              # the table's first and last rows take part
+    if N - 1 not in idx:
+        idx[1] = N - 1
+    src = workloads.uniform_f32(81, M, D)
+    dsrc, didx = torch.from_numpy(src).cuda(), torch.from_numpy(idx).cuda()
+    s = torch.cuda.current_stream().cuda_stream
+    want = t.numpy().copy()                                     # 9.6 GB on the host
+    oracle.scatter(want, idx, src)
+    print("full-size scatter: oracle done", flush=True)
+    ud.ud_scatter(t.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, dsrc.data_ptr(), s)
+    ud.ud_gather_status(s)
+    assert np.array_equal(bits(t.numpy()), bits(want))
+    del want
+    # HBM copy: scatter, then compare the written rows and a sample of untouched rows through the gather
+    ud.ud_scatter(dev.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, dsrc.data_ptr(), s)
+    out = torch.empty((M, D), dtype=torch.float32, device="cuda")
+    ud.ud_gather(dev.device_ptr, N, D, ud.UD_F32, didx.data_ptr(), ud.UD_I64, M, out.data_ptr(), s)
+    ud.ud_gather_status(s)
+    assert torch.equal(out, dsrc)
+    others = np.setdiff1d(np.random.default_rng(9).integers(0, N, 300_000), idx)[:100_000].astype(np.int64)
+    dothers = torch.from_numpy(others).cuda()
+    ud.ud_gather(dev.device_ptr, N, D, ud.UD_F32, dothers.data_ptr(), ud.UD_I64, others.size, out.data_ptr(), s)
+    ud.ud_gather_status(s)
+    assert np.array_equal(bits(out[: others.size].cpu().numpy()), bits(t.numpy()[others]))   # t now equals the oracle's table
+    dev.free()
+    t.free()
