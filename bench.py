@@ -571,10 +571,14 @@ def wl_overlap(env, quick=False, table=None):
     def timed(fn):
         fn()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3
+        best = None
+        for _ in range(2):                                   # the better of two: co-scheduling of two streams is jittery
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3
+            best = ms if best is None or ms < best else best
+        return best
 
     def only_gather(tun):
         def f():
@@ -629,7 +633,7 @@ def wl_overlap(env, quick=False, table=None):
         return f
 
     T = ud.ud_tuning
-    shapes = [("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("128wg", T(0, 0, 0, 128, 0)), ("64wg", T(0, 0, 0, 64, 0)),
+    shapes = [("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("128wg_1row", T(0, 0, 1, 128, 0)), ("64wg_1row", T(0, 0, 1, 64, 0)),
               ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU)), ("32wg_of_1024", T(0, 0, 0, 32, ud.UD_TUNE_BIG_BLOCKS))]
     if not quick:
         shapes += [("256wg", T(0, 0, 0, 256, 0)), ("64wg_4rows_in_flight", T(0, 1, 4, 64, 0)),
@@ -652,7 +656,7 @@ def wl_overlap(env, quick=False, table=None):
     consumer["passes"] = max(1, round(8 * t_c / t_e))
     t_e = timed(only_compute) / nb
     elementwise = {"compute_only_ms": round(t_e, 3), "passes": consumer["passes"]}
-    for name, tun in (("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("64wg", T(0, 0, 0, 64, 0)),
+    for name, tun in (("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("64wg_1row", T(0, 0, 1, 64, 0)),
                       ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU))):
         tg = timed(only_gather(tun)) / nb
         to = timed(overlapped(tun)) / nb
@@ -674,9 +678,10 @@ def wl_overlap(env, quick=False, table=None):
             "compute_only_ms": round(t_c, 3), "variants": variants, "elementwise_consumer": elementwise, "parity_spot_check": ok}
 
 
-def wl_padded(env, quick=False):
+def wl_padded(env, quick=False, dense_table=None):
     """The same gathers from tables whose row pitch is rounded up to 128 bytes (UD_TABLE_PAD_ROWS): no row shares
-    a memory line with its neighbours, so nothing but the row's own lines is fetched."""
+    a memory line with its neighbours, so nothing but the row's own lines is fetched.  quick: the D=602 fp32 case
+    only, its dense side being the table given."""
     ud, torch, np, workloads = env.ud, env.torch, env.np, env.workloads
     oracle = env.oracle
     N, M, W = N_ROWS, M_ROWS, env.W
@@ -684,17 +689,21 @@ def wl_padded(env, quick=False):
     reps = 4 if quick else min(env.K, 10)
     cases, ok = {}, True
     tot_b = tot_ms = 0.0
-    for name, elem, dtype, odtype, D in (("f32_D100", ud.UD_F32, ud.UD_F32, oracle.F32, 100),
-                                         ("f32_D602", ud.UD_F32, ud.UD_F32, oracle.F32, 602),
-                                         ("f16_to_f32_D602", ud.UD_F16, ud.UD_F16_TO_F32, oracle.F16_TO_F32, 602)):
+    todo = (("f32_D100", ud.UD_F32, ud.UD_F32, oracle.F32, 100), ("f32_D602", ud.UD_F32, ud.UD_F32, oracle.F32, 602),
+            ("f16_to_f32_D602", ud.UD_F16, ud.UD_F16_TO_F32, oracle.F16_TO_F32, 602))
+    if quick:
+        todo = todo[1:2]
+    for name, elem, dtype, odtype, D in todo:
         esz = 4 if elem == ud.UD_F32 else 2
         ids_np = [workloads.indices_uniform(workloads.IDX_STREAM + k, M, N) for k in range(reps + W)]
         ids_dev = [torch.from_numpy(a).to(env.dev) for a in ids_np]
         out = torch.empty(M * D, dtype=torch.float32, device=env.dev)
         r = {}
         for kind, flags in (("dense", 0), ("padded", ud.UD_TABLE_PAD_ROWS)):
-            t = ud.Table(N, D, elem, flags)
-            (workloads.fill_uniform_f32 if elem == ud.UD_F32 else workloads.fill_normal_f16)(t.host_ptr, 9, N * t.pitch)
+            given = kind == "dense" and dense_table is not None and dense_table.D == D and dense_table.elem == elem
+            t = dense_table if given else ud.Table(N, D, elem, flags)
+            if not given:
+                (workloads.fill_uniform_f32 if elem == ud.UD_F32 else workloads.fill_normal_f16)(t.host_ptr, 9, N * t.pitch)
             ms = env.event_times(lambda k: ud.ud_gather_pitched(t.device_ptr, N, D, t.pitch, dtype, ids_dev[k].data_ptr(), ud.UD_I64, M,
                                                                 out.data_ptr(), stream), len(ids_dev), W)
             st = _stats(ms)
@@ -706,13 +715,14 @@ def wl_padded(env, quick=False):
             if kind == "padded":
                 tot_b += useful
                 tot_ms += st["median_ms"]
-            t.free()
+            if not given:
+                t.free()
         r["speedup"] = round(r["dense"]["ms"] / r["padded"]["ms"], 3)
         cases[name] = r
     return {"value": tot_b / tot_ms / 1e6, "ms_per_step": tot_ms, "dtype": "f32",
             "config": {"workload": "padded rows: 1,000,000 int64 IDs from 4,000,000-row host-pinned tables with the row pitch "
                                    "rounded up to 128 bytes, against the dense layout; value = useful bytes / time, padded tables"},
-            "cases": cases, "parity_spot_check": ok}
+            "padded_cases": cases, "parity_spot_check": ok}
 
 
 def wl_fp16(env, quick=False):
@@ -900,6 +910,10 @@ def _embed(env, res):
         out["cases"] = {name: {"plain_zero_copy_GBps": c["plain_zero_copy_GBps"],
                                "caches": {f: [v["rows_cached"], v["hit_fraction_batch0"], v["effective_GBps"], v["speedup_vs_plain"]]
                                           for f, v in c["caches"].items()}} for name, c in res["cases"].items()}
+    if "padded_cases" in res:           # 128-byte row pitch against the dense layout
+        out["columns"] = ["pitch_bytes", "GBps", "frac_of_h2d_peak"]
+        out["cases"] = {name: {k: ([v["pitch_bytes"], v["GBps"], v["frac_of_h2d_peak"]] if isinstance(v, dict) else v)
+                               for k, v in c.items()} for name, c in res["padded_cases"].items()}
     if "variants" in res:               # overlap with a consumer
         out["columns"] = ["gather_only_ms", "overlapped_ms", "hidden_fraction_of_gather"]
         out["gemm_consumer"] = {k: [v["gather_only_ms"], v["overlapped_ms"], v["hidden_fraction_of_gather"]] for k, v in res["variants"].items()}
@@ -944,6 +958,7 @@ def run_everything_else(env, sweep_table):
         env.torch.cuda.synchronize()
 
     run("align_fig7", experiments, lambda: wl_align(env, True, sweep_table))
+    run("padded_rows", experiments, lambda: wl_padded(env, True, sweep_table))
     run("scatter", experiments, lambda: wl_scatter(env, True, sweep_table))
     sweep_table.free()
     run("config1_single", configs, lambda: wl_single(env, True))
