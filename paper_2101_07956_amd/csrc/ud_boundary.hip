@@ -115,10 +115,17 @@ int find_slot(SlotTable &t, hipStream_t stream, bool claim, bool share_last)
         return t.used++;
     }
     for (int k = 0; k < t.used; ++k)
-        if (!t.busy[k].load(std::memory_order_acquire)) {      // idle since its owner's last status call
-            t.owner[k] = stream;
-            g_slot_generation.fetch_add(1, std::memory_order_release);
-            return k;
+        if (!t.busy[k].load()) {                               // idle since its owner's last status call
+            // The old owner's thread may be about to launch again through its per-thread shortcut, which marks
+            // the slot busy first and compares the generation afterwards.  Bumping the generation first and
+            // taking the slot only if it is still idle means exactly one side gets it: a shortcut that marked
+            // it busy before this exchange keeps the slot, one that comes later sees the new generation.
+            g_slot_generation.fetch_add(1);
+            bool idle = false;
+            if (t.busy[k].compare_exchange_strong(idle, true)) {
+                t.owner[k] = stream;
+                return k;
+            }
         }
     return share_last ? kErrSlots - 1 : -1;
 }
@@ -149,11 +156,14 @@ ud_status error_slot(hipStream_t stream, bool fixed, unsigned long long **w)
     if (st != UD_OK)
         return st;
     const int f = fixed ? 1 : 0;
-    if (last_slot[f] && dev == last_dev[f] && stream == last_stream[f] &&
-        last_generation[f] == g_slot_generation.load(std::memory_order_acquire)) {
-        last_busy[f]->store(true, std::memory_order_release);
-        *w = last_slot[f];
-        return UD_OK;
+    if (last_slot[f] && dev == last_dev[f] && stream == last_stream[f]) {
+        // busy first, generation second (see find_slot): if the slot went to another stream in between,
+        // the generation has moved and the slow path finds this stream a slot of its own
+        last_busy[f]->store(true);
+        if (last_generation[f] == g_slot_generation.load()) {
+            *w = last_slot[f];
+            return UD_OK;
+        }
     }
     std::lock_guard<std::mutex> lock(g_err_mutex);
     SlotTable &t = fixed ? g_dev[dev].fixed : g_dev[dev].heap;
@@ -677,9 +687,11 @@ static ud_status scatter_impl(void *table, int64_t N, int64_t D, int64_t pitch, 
         plan.max_blocks = 512;         // the write direction's own optimum for long rows behind the host link
     const bool flat_ok = ud::flat_supports(N, D, pitch * elem_bytes(dtype), M);
     if (hbm && flat_ok && !tuning) {
-        // streaming stores: +8% at 400- and 2408-byte rows, nothing on multiples of 128 bytes, a loss at 64 bytes
-        plan.flags = UD_TUNE_FLAT_SOURCE | (D * elem_bytes(dtype) > 64 ? UD_TUNE_NT_STORE : 0u);
-        plan.chunks_per_lane = kScatterFlatChunks;
+        // streaming stores: +8% at 400- and 2408-byte rows, nothing on longer multiples of 128 bytes; rows up to
+        // 256 bytes gain 4-14% from streaming stores together with two chunks per lane, longer rows lose 5% to
+        // the second chunk
+        plan.flags = UD_TUNE_FLAT_SOURCE | UD_TUNE_NT_STORE;
+        plan.chunks_per_lane = D * elem_bytes(dtype) <= 256 ? 2 : kScatterFlatChunks;
         plan.max_blocks = kDefaultMaxBlocks;
     }
     if (tuning) {
@@ -732,9 +744,9 @@ static ud_status scatter_impl(void *table, int64_t N, int64_t D, int64_t pitch, 
     const ud_status es = error_slot(static_cast<hipStream_t>(stream), false, &a.err);
     if (es != UD_OK)
         return es;
-    const hipError_t e = (plan.flags & UD_TUNE_FLAT_SOURCE)
-                             ? ud::launch_scatter_flat(a, elem_bytes(dtype), plan, static_cast<hipStream_t>(stream))
-                             : ud::launch_scatter(a, elem_bytes(dtype), plan, static_cast<hipStream_t>(stream));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t e = (plan.flags & UD_TUNE_FLAT_SOURCE) ? ud::launch_scatter_flat(a, elem_bytes(dtype), plan, s)
+                                                            : ud::launch_scatter(a, elem_bytes(dtype), plan, s);
     if (e == hipErrorInvalidValue)
         return UD_ERR_UNSUPPORTED;
     if (e != hipSuccess)

@@ -565,6 +565,60 @@ def test_more_streams_than_error_slots(ud):
     t.free()
 
 
+def test_error_slots_change_hands_between_host_threads(ud):
+    # four host threads, each driving its own 40 streams (160 streams for 63 slots): every launch is followed by its
+    # status call, so slots are idle most of the time and are handed from stream to stream across threads all
+    # the time; each report must be exactly what that stream was given
+    import threading
+    N, D, M = 3000, 64, 2000
+    t = make_table(ud, N, D, ud.UD_F32, 71)
+    idx = workloads.indices_uniform(72, M, N)
+    want = oracle_bits(t.numpy(), idx, oracle.F32)
+    bad_positions = (0, 777, M - 1)
+    d_ids = [torch.from_numpy(idx).cuda()]
+    for pos in bad_positions:
+        b = idx.copy()
+        b[pos] = N + pos
+        d_ids.append(torch.from_numpy(b).cuda())
+    n_threads, per_thread, rounds = 4, 40, 3
+    outs = [torch.zeros((M, D), dtype=torch.float32, device="cuda") for _ in range(n_threads)]
+    torch.cuda.synchronize()
+    from conftest import RawStreams
+    streams = RawStreams(n_threads * per_thread)
+    failures = []
+
+    def drive(k):
+        try:
+            mine = streams.handles[k * per_thread:(k + 1) * per_thread]
+            for r in range(rounds):
+                for j, st in enumerate(mine):
+                    which = (k + 3 * j + r) % 4                 # 0: clean, else a bad ID at bad_positions[which - 1]
+                    ud.ud_gather(t.device_ptr, N, D, ud.UD_F32, d_ids[which].data_ptr(), ud.UD_I64, M, outs[k].data_ptr(), st)
+                    try:
+                        ud.ud_gather_status(st)
+                        got = None
+                    except ud.UdIndexError as e:
+                        got = e.pos
+                    expect = None if which == 0 else bad_positions[which - 1]
+                    if got != expect:
+                        failures.append((k, r, j, which, got))
+                    if which == 0 and j % 8 == 0 and not np.array_equal(outs[k].cpu().numpy().view(np.uint32), want):
+                        failures.append((k, r, j, "data"))
+        except Exception as e:                                   # noqa: BLE001 - reported by the main thread
+            failures.append((k, repr(e)))
+
+    threads = [threading.Thread(target=drive, args=(k,)) for k in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not failures, failures[:5]
+    for st in streams.handles:
+        ud.ud_gather_status(st)
+    streams.close()
+    t.free()
+
+
 def test_gathers_captured_in_a_hip_graph_replay_correctly(ud):
     # a launch-bound inner loop (several small gathers) captured once and replayed with new IDs each time;
     # the first eager call is what allocates the library's error word, so it runs before capture

@@ -202,9 +202,12 @@ def test_rows_shorter_than_a_chunk_with_an_unaligned_table_base(ud, esz, D):
             oracle.scatter(want_all[shift:shift + N * D].reshape(N, D), idx, src)
             dsrc = torch.from_numpy(src.view(np.int32 if esz == 4 else np.int16)).cuda()
             didx = torch.from_numpy(idx).cuda()
-            ud.ud_scatter(big.device_ptr + shift * esz, N, D, dtype, didx.data_ptr(), ud.UD_I64, M, dsrc.data_ptr(), s)
-            ud.ud_gather_status(s)
-            assert np.array_equal(storage, want_all), (esz, D, shift, M)
+            before = storage.copy()
+            for tun in (None, ud.ud_tuning(0, 1, 0, 0, ud.UD_TUNE_FLAT_SOURCE), ud.ud_tuning(0, 4, 0, 0, ud.UD_TUNE_FLAT_SOURCE)):
+                storage[:] = before
+                ud.ud_scatter(big.device_ptr + shift * esz, N, D, dtype, didx.data_ptr(), ud.UD_I64, M, dsrc.data_ptr(), s, tun)
+                ud.ud_gather_status(s)
+                assert np.array_equal(storage, want_all), (esz, D, shift, M, tun and tun.flags)
             big.free()
 
 
