@@ -112,6 +112,12 @@ def replay_shapes(ud):
     for D in (100, 602):
         shapes.append((f"scatter hbm f32 D={D} row-per-lane-group kernel", "scatter", ud.UD_F32, D, "hbm", "perm", T(0, 0, 0, 0, 0)))
     shapes.append(("scatter hbm f32 D=96 auto (384-byte rows: whole lines)", "scatter", ud.UD_F32, 96, "hbm", "perm", None))
+    # row ends on 32-byte and on 64-byte boundaries, with and without streaming stores
+    FS = ud.UD_TUNE_FLAT_SOURCE
+    shapes.append(("scatter hbm f32 D=104 auto (416-byte rows)", "scatter", ud.UD_F32, 104, "hbm", "perm", None))
+    shapes.append(("scatter hbm f32 D=112 auto (448-byte rows)", "scatter", ud.UD_F32, 112, "hbm", "perm", None))
+    shapes.append(("scatter hbm f32 D=112 same kernel, ordinary stores", "scatter", ud.UD_F32, 112, "hbm", "perm", T(0, 1, 0, 0, FS)))
+    shapes.append(("scatter hbm f32 D=100 same kernel, ordinary stores", "scatter", ud.UD_F32, 100, "hbm", "perm", T(0, 1, 0, 0, FS)))
     return shapes
 
 
