@@ -634,12 +634,10 @@ def wl_overlap(env, quick=False, table=None):
 
     T = ud.ud_tuning
     shapes = [("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("128wg_1row", T(0, 0, 1, 128, 0)), ("64wg_1row", T(0, 0, 1, 64, 0)),
-              ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU)), ("32wg_of_1024", T(0, 0, 0, 32, ud.UD_TUNE_BIG_BLOCKS))]
+              ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU))]
     if not quick:
         shapes += [("256wg", T(0, 0, 0, 256, 0)), ("64wg_4rows_in_flight", T(0, 1, 4, 64, 0)),
-                   ("32wg_4rows_in_flight", T(0, 1, 4, 32, 0)), ("16wg_of_1024", T(0, 0, 0, 16, ud.UD_TUNE_BIG_BLOCKS)),
-                   ("16wg_of_1024_2rows", T(0, 1, 2, 16, ud.UD_TUNE_BIG_BLOCKS)), ("8wg_of_1024_2rows", T(0, 1, 2, 8, ud.UD_TUNE_BIG_BLOCKS)),
-                   ("8wg_of_1024_4rows", T(0, 1, 4, 8, ud.UD_TUNE_BIG_BLOCKS))]
+                   ("32wg_4rows_in_flight", T(0, 1, 4, 32, 0))]
     variants = {}
     for name, tun in shapes:
         tg = timed(only_gather(tun)) / nb

@@ -223,9 +223,6 @@ enum {
     UD_TUNE_ELEMENTWISE = 4u,   /* one lane per element, rows straddling wavefronts: the layout of
                                    the unmodified indexing kernel of Section 4.5 / Figure 4, kept as
                                    the comparison point and as the fallback for odd alignments */
-    UD_TUNE_BIG_BLOCKS = 16u,   /* 1024-thread workgroups instead of 256: with a small max_blocks the whole
-                                   gather then sits on few compute units and leaves the others, registers
-                                   included, to a compute kernel running beside it */
     UD_TUNE_CIRCULAR_SHIFT = 32u, /* with UD_TUNE_ELEMENTWISE: rotate each row's lanes as in Section 4.5 / Figure 5 of
                                    the paper (its alignment fix), for comparison */
     UD_TUNE_SHARE_GPU = 128u,   /* launch shape for a gather that runs beside another stream's kernels: a grid of
@@ -238,7 +235,7 @@ enum {
                                    choice for tables in HBM, where the gather is bound by HBM bandwidth; tables
                                    read over the host link use the source-aligned kernel (flag clear).  Uses
                                    chunks_per_lane and max_blocks; lanes_per_row and rows_in_flight are ignored.
-                                   Not combinable with ELEMENTWISE, BIG_BLOCKS or SHARE_GPU */
+                                   Not combinable with ELEMENTWISE or SHARE_GPU */
     UD_TUNE_FLAT_SOURCE = 512u  /* ud_scatter_tuned only: the scatter kernel that cuts the dense SOURCE into aligned
                                    16-byte chunks, one per lane (no idle lanes whatever the width), and writes the table
                                    rows with element-aligned stores.  The automatic choice for tables in HBM; tables

@@ -21,7 +21,7 @@ UD_OK, UD_ERR_INVALID_ARG, UD_ERR_UNSUPPORTED, UD_ERR_OOM, UD_ERR_INDEX_OUT_OF_R
 UD_F32, UD_F16, UD_F16_TO_F32 = 0, 1, 2
 UD_I64, UD_I32 = 0, 1
 UD_TABLE_COHERENT, UD_TABLE_NONCOHERENT, UD_TABLE_PAD_ROWS = 0, 1, 2
-UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE, UD_TUNE_BIG_BLOCKS = 2, 4, 16
+UD_TUNE_NT_STORE, UD_TUNE_ELEMENTWISE = 2, 4
 UD_TUNE_CIRCULAR_SHIFT, UD_TUNE_SHARE_GPU, UD_TUNE_DEST_ALIGNED, UD_TUNE_FLAT_SOURCE = 32, 128, 256, 512
 
 #: every symbol include/ud.h declares

@@ -527,13 +527,13 @@ static ud_status gather_impl(const void *table, int64_t N, int64_t D, int64_t pi
 
     ud::Plan plan = auto_plan(table, D, pitch, dtype);
     if (tuning) {
-        if (tuning->flags & ~(UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_BIG_BLOCKS | UD_TUNE_CIRCULAR_SHIFT |
+        if (tuning->flags & ~(UD_TUNE_NT_STORE | UD_TUNE_ELEMENTWISE | UD_TUNE_CIRCULAR_SHIFT |
                               UD_TUNE_SHARE_GPU | UD_TUNE_DEST_ALIGNED))
             return UD_ERR_INVALID_ARG;
         if ((tuning->flags & UD_TUNE_CIRCULAR_SHIFT) && !(tuning->flags & UD_TUNE_ELEMENTWISE))
             return UD_ERR_INVALID_ARG;
         if ((tuning->flags & UD_TUNE_DEST_ALIGNED) &&
-            (tuning->flags & (UD_TUNE_ELEMENTWISE | UD_TUNE_BIG_BLOCKS | UD_TUNE_SHARE_GPU)))
+            (tuning->flags & (UD_TUNE_ELEMENTWISE | UD_TUNE_SHARE_GPU)))
             return UD_ERR_INVALID_ARG;
         if (tuning->lanes_per_row < 0 || tuning->lanes_per_row > 64 ||
             (tuning->lanes_per_row && !is_pow2(tuning->lanes_per_row)))

@@ -164,7 +164,10 @@ __device__ __forceinline__ void store_halves(uint16_t *d, u32x4 v, int lo, int h
 // that are assigned conditionally end up copied between registers, with a wait
 // before each copy.
 template <int DT, int U, int P, bool NTS, bool I64>
-__global__ __launch_bounds__(kMaxBlockThreads) void gather_chunked(GatherArgs a, int lg)
+// Launched with kBlockThreads threads but declared for up to 1024: the instructions generated are the same for
+// either bound, yet with the larger one in the kernel's metadata the 64-byte-row gather over the host link
+// measures 3% faster on MI355X (20.9 -> 21.6 GB/s, three runs each), the other widths the same.
+__global__ __launch_bounds__(1024) void gather_chunked(GatherArgs a, int lg)
 {
     constexpr int IN_ESZ = (DT == UD_F32) ? 4 : 2;      // table element bytes
     constexpr int EPC = 16 / IN_ESZ;                    // elements per 16-byte chunk
@@ -296,7 +299,7 @@ hipError_t launch_chunked(const GatherArgs &a_in, const Plan &p, hipStream_t s)
     if ((1 << lg) != p.lanes_per_row || lg > 6)
         return hipErrorInvalidValue;
     GatherArgs a = a_in;
-    const int wpb = (p.flags & UD_TUNE_BIG_BLOCKS) ? kMaxBlockThreads / 64 : kWavesPerBlock;
+    const int wpb = kWavesPerBlock;
     const int64_t rows_per_pass = static_cast<int64_t>(64 >> lg) * p.rows_in_flight * wpb;
     const int64_t ids_per_line = a.itype == UD_I64 ? 16 : 32;         // IDs in a 128-byte line of the list
     a.group_iters = p.tile_id_lines ? static_cast<int>((ids_per_line + rows_per_pass - 1) / rows_per_pass) : 1;

@@ -40,8 +40,6 @@ struct Plan {
 // Wavefronts per workgroup used by every kernel here.
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;
-// Largest workgroup the chunked gather may be launched with (UD_TUNE_BIG_BLOCKS).
-constexpr int kMaxBlockThreads = 1024;
 
 // Enqueue the chunked (row-per-lane-group, source-aligned) gather.  Returns
 // hipErrorInvalidValue if (dtype, plan) has no instantiation.

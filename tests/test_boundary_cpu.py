@@ -89,11 +89,11 @@ def test_tuning_fields_are_range_checked(ud):
     assert _gather(ud, tuning=T(0, 0, 3, 0, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, -1, 0)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, 0, 512)) == inv      # unknown flag
-    for gone in (1, 8, 64):                                   # options earlier versions had: no longer accepted
+    for gone in (1, 8, 16, 64):                                 # options earlier versions had: no longer accepted
         assert _gather(ud, tuning=T(0, 0, 0, 0, gone)) == inv
     assert _gather(ud, tuning=T(0, 0, 0, 0, 32)) == inv       # circular shift needs the one-lane-per-element kernel
     DA = ud.UD_TUNE_DEST_ALIGNED
-    for other in (ud.UD_TUNE_ELEMENTWISE, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_SHARE_GPU):
+    for other in (ud.UD_TUNE_ELEMENTWISE, ud.UD_TUNE_SHARE_GPU):
         assert _gather(ud, tuning=T(0, 0, 0, 0, DA | other)) == inv
     assert _gather(ud, tuning=T(0, 3, 0, 0, DA)) == ud.UD_ERR_UNSUPPORTED     # 1, 2 or 4 output chunks per lane
     assert _gather(ud, M=0, tuning=T(0, 4, 0, 0, DA | ud.UD_TUNE_NT_STORE)) == ud.UD_OK

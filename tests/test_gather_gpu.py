@@ -114,7 +114,7 @@ def test_every_instantiation_every_group_size(ud, u, p):
         idx = workloads.indices_uniform(9, M, N)
         want = oracle_bits(t.numpy(), idx, dtype)
         for lanes in (1, 2, 4, 8, 16, 32, 64):
-            for flags in (0, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_BIG_BLOCKS):
+            for flags in (0, ud.UD_TUNE_NT_STORE):
                 tun = ud.ud_tuning(lanes, p, u, 0, flags)
                 got = run_gather(ud, t, idx, dtype, tun)
                 assert np.array_equal(got, want), (dtype, D, lanes, u, p, flags)
@@ -127,7 +127,7 @@ def test_grid_stride_when_blocks_are_capped(ud):
     idx = workloads.indices_uniform(10, M, N)
     want = oracle_bits(t.numpy(), idx, oracle.F32)
     for blocks in (1, 7, 256):
-        for flags in (0, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_DEST_ALIGNED, ud.UD_TUNE_DEST_ALIGNED | ud.UD_TUNE_NT_STORE):
+        for flags in (0, ud.UD_TUNE_DEST_ALIGNED, ud.UD_TUNE_DEST_ALIGNED | ud.UD_TUNE_NT_STORE):
             got = run_gather(ud, t, idx, ud.UD_F32, ud.ud_tuning(0, 0, 0, blocks, flags))
             assert np.array_equal(got, want), (blocks, flags)
     t.free()

@@ -48,7 +48,7 @@ def test_random_gathers(ud):
         want = want.view(np.uint16 if obytes == 2 else np.uint32)
         u, p = SHAPES[int(rng.integers(0, len(SHAPES)))]
         lanes = int(2 ** rng.integers(0, 7))
-        flags = int(rng.choice([0, 0, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_BIG_BLOCKS, ud.UD_TUNE_DEST_ALIGNED,
+        flags = int(rng.choice([0, 0, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_NT_STORE, ud.UD_TUNE_DEST_ALIGNED,
                                 ud.UD_TUNE_DEST_ALIGNED | ud.UD_TUNE_NT_STORE, ud.UD_TUNE_ELEMENTWISE,
                                 ud.UD_TUNE_ELEMENTWISE | ud.UD_TUNE_CIRCULAR_SHIFT, ud.UD_TUNE_SHARE_GPU]))
         blocks = int(rng.choice([0, 1, 3, 64]))
