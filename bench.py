@@ -869,7 +869,6 @@ def _round_floats(x, nd=3):
 def _embed(env, res):
     """A workload's result boiled down for the all-in-one line (the line has to stay well below what the harness
     keeps of stdout); the full dictionaries go to gpurun_out/bench_details.json."""
-    r4 = lambda x: None if x is None else round(x, 4)
     out = {"GBps": round(res["value"], 2), "frac_of_h2d_peak": round(res["value"] / env.h2d_peak, 4),
            "ms_per_step": round(res["ms_per_step"], 4), "dtype": res["dtype"], "parity_spot_check": res.get("parity_spot_check")}
     if "kernel_only" in res:

@@ -271,7 +271,6 @@ def _summarise(timing_path: str, csv_paths, out_path, traffic_note=None, only=No
     w("# req128/row = TCC_EA0_RDREQ_128B per gathered row; stalls = TCC_EA0_RDREQ_{IO,DRAM}_CREDIT_STALL (cycles summed over channels).")
     w("")
     hdr = f"{'shape':64s} {'ms':>9s} {'GB/s':>9s} {'%peak':>6s} {'peak':>9s}"
-    extra_cols = []
     if fscale:
         hdr += f" {'fetch_MB':>9s} {'floor_MB':>9s} {'fetch/floor':>11s}"
     if wscale:

@@ -1,6 +1,4 @@
 """GPU parity of the write direction (ud_scatter) against the oracle, bit for bit."""
-import itertools
-
 import numpy as np
 import pytest
 
