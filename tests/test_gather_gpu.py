@@ -438,10 +438,24 @@ def test_single_row_table_and_single_id(ud):
 
 
 def test_very_wide_rows(ud):
-    N, D, M = 37, 100_003, 29                  # 400 KB rows: many chunk blocks per row
+    N, D, M = 37, 100_003, 29                  # 400 KB rows: many chunk blocks per row, a row far longer than a wavefront tile
     t = make_table(ud, N, D, ud.UD_F32, 53)
     idx = workloads.indices_uniform(54, M, N)
-    assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32), oracle_bits(t.numpy(), idx, oracle.F32))
+    want = oracle_bits(t.numpy(), idx, oracle.F32)
+    assert np.array_equal(run_gather(ud, t, idx, ud.UD_F32), want)
+    dev = t.to_device()                         # the destination-aligned kernel
+    assert np.array_equal(run_gather(ud, dev, idx, ud.UD_F32), want)
+    for P in (1, 4):
+        assert np.array_equal(run_gather(ud, dev, idx, ud.UD_F32, tuning=ud.ud_tuning(0, P, 0, 5, ud.UD_TUNE_DEST_ALIGNED)), want)
+    dev.free()
+    t.free()
+    # the same in half precision, widened: 200 KB rows in, 400 KB rows out
+    t = make_table(ud, N, D, ud.UD_F16, 55)
+    want = oracle_bits(t.numpy(), idx, oracle.F16_TO_F32)
+    assert np.array_equal(run_gather(ud, t, idx, ud.UD_F16_TO_F32), want)
+    dev = t.to_device()
+    assert np.array_equal(run_gather(ud, dev, idx, ud.UD_F16_TO_F32), want)
+    dev.free()
     t.free()
 
 

@@ -277,6 +277,31 @@ def test_source_aligned_scatter_skips_and_reports_bad_ids(ud):
     t.free()
 
 
+def test_very_wide_rows_are_scattered_whole(ud):
+    # 400 KB rows: many chunk blocks per row in the row-per-lane-group kernel, a row far longer than a wavefront
+    # tile in the source-aligned one; host table, then its HBM copy read back through the gather
+    N, D, M = 37, 100_003, 29
+    t = ud.Table(N, D, ud.UD_F32)
+    workloads.fill_uniform_f32(t.host_ptr, 90, N * D)
+    dev = t.to_device()
+    idx = distinct_ids(91, M, N)
+    src = workloads.uniform_f32(92, M, D)
+    want = t.numpy().copy()
+    oracle.scatter(want, idx, src)
+    run_scatter(ud, t, idx, src)
+    assert np.array_equal(bits(t.numpy()), bits(want))
+    for tun in (None, ud.ud_tuning(0, 4, 0, 7, ud.UD_TUNE_FLAT_SOURCE)):
+        run_scatter(ud, dev, idx, src, tun)
+        allrows = torch.arange(N, dtype=torch.int64, device="cuda")
+        out = torch.empty((N, D), dtype=torch.float32, device="cuda")
+        s = torch.cuda.current_stream().cuda_stream
+        ud.ud_gather(dev.device_ptr, N, D, ud.UD_F32, allrows.data_ptr(), ud.UD_I64, N, out.data_ptr(), s)
+        ud.ud_gather_status(s)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(want))
+    dev.free()
+    t.free()
+
+
 def test_full_size_scatter_into_the_benchmark_table(ud):
     # the write direction at the benchmark's size: 1,000,000 distinct rows x 602 fp32 into the 4,000,000-row
     # host-pinned table (9.6 GB), the whole table compared with the oracle's; then the same into its HBM copy,
