@@ -126,16 +126,18 @@ def _kernel_times(ud, torch, tptr, N, D, dtype, id_tensors, out, warm, tuning=No
     return [a.elapsed_time(b) for a, b in ev]
 
 
-def _wall_times(ud, torch, tptr, N, D, dtype, ids_pinned, out, warm):
-    """Call-to-sync wall time per gather INCLUDING the host->device copy of the ID list (pinned source)."""
+def _wall_times(ud, torch, tptr, N, D, dtype, ids_pinned, out, warm, ids_stay_in_host=False):
+    """Call-to-sync wall time per gather INCLUDING the host->device copy of the ID list (pinned source).
+    ids_stay_in_host: no copy, the kernel reads the ID list from pinned host memory as it reads the rows."""
     stream = torch.cuda.current_stream()
     dst = torch.empty(max(t.numel() for t in ids_pinned), dtype=ids_pinned[0].dtype, device="cuda")
     ms = []
     for k, ids in enumerate(ids_pinned):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        d = dst[: ids.numel()]
-        d.copy_(ids, non_blocking=True)
+        d = ids if ids_stay_in_host else dst[: ids.numel()]
+        if not ids_stay_in_host:
+            d.copy_(ids, non_blocking=True)
         ud.ud_gather(tptr, N, D, dtype, d.data_ptr(), _itype(ud, d), ids.numel(), out.data_ptr(), stream.cuda_stream)
         stream.synchronize()
         if k >= warm:
@@ -827,11 +829,16 @@ def wl_grid(env, quick=False):
             ok = ok and env.spot_check(table, N, D, env.oracle.F32, ids_np[-1], out, 512)
             nv = _stats(_kernel_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, ids_dev, out, W, naive))
             ok = ok and env.spot_check(table, N, D, env.oracle.F32, ids_np[-1], out, 128)
-            wall = _stats(_wall_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, [env.pinned(a) for a in ids_np], out, W))
+            pinned = [env.pinned(a) for a in ids_np]
+            wall = _stats(_wall_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, pinned, out, W))
+            wall_zc = _stats(_wall_times(ud, torch, table.device_ptr, N, D, ud.UD_F32, pinned, out, W, ids_stay_in_host=True))
+            ok = ok and env.spot_check(table, N, D, env.oracle.F32, ids_np[-1], out, 128)
             ideal = nbytes / env.h2d_peak / 1e6
             c = {"MB": round(nbytes / 1e6, 2), "kernel_ms": kern["median_ms"], "one_lane_per_element_kernel_ms": nv["median_ms"],
                  "call_to_sync_ms": wall["median_ms"], "ideal_ms": round(ideal, 4),
                  "slowdown_vs_ideal": round(wall["median_ms"] / ideal, 3),
+                 "call_to_sync_ids_read_from_host_ms": wall_zc["median_ms"],
+                 "ids_read_from_host_slowdown_vs_ideal": round(wall_zc["median_ms"] / ideal, 3),
                  "one_lane_per_element_kernel_slowdown_vs_ideal": round(nv["median_ms"] / ideal, 3)}
             if have_cpu:
                 _cpu_centric(bl, ctx, table.host_ptr, rb, ids_np[0], out.data_ptr(), threads)
@@ -896,9 +903,11 @@ def _embed(env, res):
         out["per_row_bytes"] = {k: [v["zero_copy_GBps"], v["one_lane_per_element_GBps"], v["circular_shift_GBps"],
                                     v.get("cpu_centric_ms"), v["zero_copy_ms"], v["ideal_ms"]] for k, v in res["per_row_bytes"].items()}
     if "cells" in res:                  # size grid
-        out["columns"] = ["MB", "call_to_sync_x_ideal", "one_lane_per_element_kernel_x_ideal", "cpu_centric_x_ideal", "call_to_sync_ms"]
+        out["columns"] = ["MB", "call_to_sync_x_ideal", "one_lane_per_element_kernel_x_ideal", "cpu_centric_x_ideal", "call_to_sync_ms",
+                          "call_to_sync_ids_read_from_host_x_ideal"]
         out["cells"] = {k: [v["MB"], v["slowdown_vs_ideal"], v["one_lane_per_element_kernel_slowdown_vs_ideal"],
-                            v.get("cpu_centric_slowdown_vs_ideal"), v["call_to_sync_ms"]] for k, v in res["cells"].items()}
+                            v.get("cpu_centric_slowdown_vs_ideal"), v["call_to_sync_ms"], v["ids_read_from_host_slowdown_vs_ideal"]]
+                        for k, v in res["cells"].items()}
     if "per_width" in res:              # write direction
         out["columns"] = ["host_GBps", "frac_of_d2h_peak", "hbm_GBps_read_plus_write"]
         out["per_width"] = {k: [v["host_GBps"], v["frac_of_d2h_peak"], v["hbm_GBps_read_plus_write"]] for k, v in res["per_width"].items()}
