@@ -107,8 +107,11 @@ ud_status ud_free_table(ud_table *t);
  *   table  device pointer to N x D elements (host-mapped or HBM), aligned to its
  *          element size; read only.
  *   dtype  UD_F32, UD_F16 or UD_F16_TO_F32 (conv = identity on bits, or widening).
- *   idx    device pointer (HBM) to M IDs of type itype; the paper's index is a
- *          GPU tensor (Table 1).  Duplicates allowed.  Never read by the CPU.
+ *   idx    device pointer to M IDs of type itype, normally in HBM (the paper's
+ *          index is a GPU tensor, Table 1); any GPU-readable memory works, so a
+ *          small ID list may stay in pinned host memory and be read over the link
+ *          like the rows, which saves its copy.  Duplicates allowed.  Never read
+ *          by the CPU.
  *   out    device pointer (HBM) to M x D output elements (4-byte for UD_F32 and
  *          UD_F16_TO_F32, 2-byte for UD_F16), aligned to its element size; must
  *          not overlap table.
@@ -240,8 +243,9 @@ enum {
                                    16-byte chunks, one per lane (no idle lanes whatever the width), and writes the table
                                    rows with element-aligned stores.  The automatic choice for tables in HBM; tables
                                    behind the host link take the kernel that writes whole aligned chunks of the table
-                                   (flag clear).  Uses chunks_per_lane (1, 2 or 4) and max_blocks; may be combined with
-                                   UD_TUNE_NT_STORE (streaming stores to the table) */
+                                   (flag clear).  Uses chunks_per_lane (1, 2 or 4; automatic: 2 for rows up to 256
+                                   bytes, else 1) and max_blocks; may be combined with UD_TUNE_NT_STORE (streaming
+                                   stores to the table, which the automatic choice uses) */
 };
 
 /* ud_gather with explicit kernel parameters (for the tuning loop and for tests that
@@ -296,8 +300,9 @@ ud_status ud_gather_plan(const void *table, int64_t D, ud_dtype dtype, ud_tuning
  * launches for the first time takes over the record of a stream that has launched nothing since its
  * own last ud_gather_status call; if there is none, it shares one common record with all other
  * streams in that position.  A stream handle that is destroyed and handed out again by the runtime
- * inherits its predecessor's record.  A stream is driven by one thread at a time.  Gathers replayed from a HIP graph report
- * to the record of the stream they were captured on: synchronise the replay, then query that stream.
+ * inherits its predecessor's record.  A stream is driven by one thread at a time; different threads
+ * may drive different streams concurrently.  Gathers replayed from a HIP graph report to the record
+ * of the stream they were captured on: synchronise the replay, then query that stream.
  * Not to be called while `stream` is being captured.
  */
 ud_status ud_gather_status(void *stream, int64_t *bad_pos);
