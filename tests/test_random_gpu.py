@@ -100,7 +100,8 @@ def test_random_scatters(ud):
         u, p = shapes[int(rng.integers(0, len(shapes)))]
         tun = None if rng.random() < 0.3 else ud.ud_tuning(int(2 ** rng.integers(0, 7)), p, u, int(rng.choice([0, 1, 5])), 0)
         if rng.random() < 0.35:                                  # the source-aligned kernel
-            tun = ud.ud_tuning(0, int(rng.choice([0, 1, 2, 4])), 0, int(rng.choice([0, 1, 5])), ud.UD_TUNE_FLAT_SOURCE)
+            tun = ud.ud_tuning(0, int(rng.choice([0, 1, 2, 4])), 0, int(rng.choice([0, 1, 5])),
+                               ud.UD_TUNE_FLAT_SOURCE | (ud.UD_TUNE_NT_STORE if rng.random() < 0.5 else 0))
         tag = (case, D, N, M, shift, esz, tun is None)
         print("scatter case", tag, flush=True)
         dsrc = torch.from_numpy(src.view(np.int32 if esz == 4 else np.int16)).cuda()
