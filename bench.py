@@ -656,8 +656,8 @@ def wl_overlap(env, quick=False, table=None):
     consumer["passes"] = max(1, round(8 * t_c / t_e))
     t_e = timed(only_compute) / nb
     elementwise = {"compute_only_ms": round(t_e, 3), "passes": consumer["passes"]}
-    for name, tun in (("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("64wg_1row", T(0, 0, 1, 64, 0)),
-                      ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU))):
+    for name, tun in (("auto", None), ("512wg_1row", T(0, 0, 1, 512, 0)), ("128wg_1row", T(0, 0, 1, 128, 0)),
+                      ("64wg_1row", T(0, 0, 1, 64, 0)), ("share_gpu_flag", T(0, 0, 0, 0, ud.UD_TUNE_SHARE_GPU))):
         tg = timed(only_gather(tun)) / nb
         to = timed(overlapped(tun)) / nb
         elementwise[name] = {"gather_only_ms": round(tg, 3), "overlapped_ms": round(to, 3),
