@@ -1181,7 +1181,11 @@ def main() -> int:
     if args.headline_only:
         table.free()
     else:
-        configs, experiments, extras_seconds = run_everything_else(env, table)
+        try:
+            configs, experiments, extras_seconds = run_everything_else(env, table)
+        except Exception as e:                       # whatever escapes the per-entry handling: the headline still prints
+            configs = experiments = {"all": {"error": f"{type(e).__name__}: {e}", "parity_spot_check": False}}
+            extras_seconds = {}
     line = {
         "metric": "zero_copy_gather_GBps",
         "value": round(value, 3),
