@@ -77,7 +77,8 @@ class Cache:
 
 
 def gather(table: Table, idx, out=None, widen: bool = False, tuning: B.ud_tuning | None = None, check: bool = False):
-    """``out[i, :] = table[idx[i], :]`` for a torch int64/int32 CUDA tensor ``idx``.
+    """``out[i, :] = table[idx[i], :]`` for a torch int64/int32 tensor ``idx`` in GPU memory, or in pinned host
+    memory (the kernel then reads the IDs over the link like the rows: no copy, worth it for small batches).
 
     Enqueues on torch's current stream and returns the output tensor (allocated
     here when ``out`` is None).  ``widen`` turns an fp16 table into fp32 output.
@@ -85,7 +86,8 @@ def gather(table: Table, idx, out=None, widen: bool = False, tuning: B.ud_tuning
     """
     import torch
 
-    assert idx.is_cuda and idx.dim() == 1 and idx.is_contiguous()
+    assert (idx.is_cuda or idx.is_pinned()) and idx.dim() == 1 and idx.is_contiguous()
+    device = idx.device if idx.is_cuda else torch.device("cuda", torch.cuda.current_device())
     itype = {torch.int64: B.UD_I64, torch.int32: B.UD_I32}[idx.dtype]
     if table.elem == B.UD_F32:
         dtype, odt = B.UD_F32, torch.float32
@@ -95,9 +97,9 @@ def gather(table: Table, idx, out=None, widen: bool = False, tuning: B.ud_tuning
         dtype, odt = B.UD_F16, torch.float16
     M = idx.numel()
     if out is None:
-        out = torch.empty((M, table.D), dtype=odt, device=idx.device)
+        out = torch.empty((M, table.D), dtype=odt, device=device)
     assert out.is_cuda and out.is_contiguous() and out.dtype == odt and out.numel() == M * table.D
-    stream = torch.cuda.current_stream(idx.device).cuda_stream
+    stream = torch.cuda.current_stream(device).cuda_stream
     if table.pitch != table.D:
         assert tuning is None, "explicit tuning is for dense tables"
         B.ud_gather_pitched(table.device_ptr, table.N, table.D, table.pitch, dtype, idx.data_ptr(), itype, M,

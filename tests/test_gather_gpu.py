@@ -768,6 +768,8 @@ def test_torch_convenience_wrapper(ud):
     pre = torch.empty((M, D), dtype=torch.float32, device="cuda")
     assert ud.gather(t, idx.to(torch.int32), out=pre, check=True) is pre
     assert torch.equal(pre, out)
+    pinned_ids = torch.from_numpy(idx_np).pin_memory()            # the ID list left in pinned host memory: no copy
+    assert torch.equal(ud.gather(t, pinned_ids, check=True), out)
     bad = idx.clone()
     bad[7] = N
     with pytest.raises(ud.UdIndexError):
